@@ -1,0 +1,163 @@
+/*
+ * mosaic_oracle.c -- plain CPU oracle for the mask-only logits path of a dLLM
+ * denoising step (Mosaic, arXiv 2601.06562).
+ *
+ * THIS IS TEST INFRASTRUCTURE, NOT THE PRODUCT.  It is slow on purpose, shares
+ * no code with the HIP library, and may be called only from tests, from the
+ * smoke check and from the benchmark's cpu_baseline leg.
+ *
+ * What it computes (paper section 2.1 "Diffusion": a forward pass yields
+ * logits, tokens are then picked from them for [MASK] positions; section 3
+ * observation #2 and section 4.2: computing logits only for masked tokens is
+ * pure redundancy elimination, i.e. it equals "logits for every position,
+ * then keep the masked rows").  The paper does not say how a token is picked
+ * from a row of logits; the reading taken here is the greedy one: per row the
+ * arg-max vocabulary id (lowest id on ties), the soft-max probability of that
+ * id ("confidence") and the log-sum-exp of the row.
+ *
+ * Definition, per position t (independent of the mask):
+ *   x[t,v] = sum_k H[t,k] * W[v,k]      bf16 inputs widened exactly, the sum
+ *                                       taken in fp64 and rounded once to fp32
+ *   m[t]   = max_v x[t,v]       tok[t] = min{ v : x[t,v] == m[t] }
+ *   s[t]   = sum_v exp(x[t,v]-m[t])     (fp64, on the fp32 logits)
+ *   lse[t] = m[t] + ln s[t]     conf[t] = exp(m[t]-lse[t]) = 1/s[t]
+ *   gap[t] = m[t] - max_{v != tok[t]} x[t,v]   (0 when the maximum is repeated)
+ * Selection: idx = ascending positions t with mask[t] != 0; outputs are the
+ * per-position values at idx[0..M-1].
+ *
+ * No blocking, no fusion, no reordering: one row of V logits at a time.
+ * The only liberty is that the fp64 dot product may be summed in any order
+ * (OpenMP simd reduction); its terms are exact products of bf16 values, so
+ * the fp64 sum is exact or within 1 ulp(fp64) in every order, far below the
+ * final rounding to fp32.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+static inline float bf16_to_f32(uint16_t b) {
+  uint32_t u = ((uint32_t)b) << 16;
+  float f;
+  memcpy(&f, &u, sizeof f);
+  return f;
+}
+
+/* Stable selection of the masked positions (paper section 4.2: the kernel is
+ * handed "mask indices"; ascending order is the reading taken here).
+ * mask: T bytes, nonzero = still masked.  idx: room for T entries.
+ * Returns M, the number of masked positions. */
+int64_t oracle_mask_select(const uint8_t *mask, int64_t T, int32_t *idx) {
+  int64_t M = 0;
+  for (int64_t t = 0; t < T; ++t) {
+    if (mask[t] != 0) {
+      idx[M] = (int32_t)t;
+      M += 1;
+    }
+  }
+  return M;
+}
+
+/* One row of logits: x[v] = fp32( sum_k h[k] * W[v,k] ), fp64 accumulation.
+ * h: d bf16 values; W: V rows of d bf16 values (row stride d). */
+void oracle_row_logits(const uint16_t *h, const uint16_t *W, int32_t d,
+                       int32_t V, float *x) {
+  double *hd = (double *)malloc(sizeof(double) * (size_t)d);
+  for (int32_t k = 0; k < d; ++k) hd[k] = (double)bf16_to_f32(h[k]);
+  for (int32_t v = 0; v < V; ++v) {
+    const uint16_t *w = W + (size_t)v * (size_t)d;
+    double acc = 0.0;
+#pragma omp simd reduction(+ : acc)
+    for (int32_t k = 0; k < d; ++k) acc += hd[k] * (double)bf16_to_f32(w[k]);
+    x[v] = (float)acc;
+  }
+  free(hd);
+}
+
+/* Reduce one row of V fp32 logits to (tok, conf, lse, gap, rowmax). */
+void oracle_row_reduce(const float *x, int32_t V, int32_t *tok, float *conf,
+                       float *lse, float *gap, float *rowmax) {
+  double m = (double)x[0];
+  int32_t arg = 0;
+  for (int32_t v = 1; v < V; ++v) {
+    if ((double)x[v] > m) { /* strict: the lowest id wins a tie */
+      m = (double)x[v];
+      arg = v;
+    }
+  }
+  double second = -INFINITY;
+  for (int32_t v = 0; v < V; ++v) {
+    if (v != arg && (double)x[v] > second) second = (double)x[v];
+  }
+  double s = 0.0;
+  for (int32_t v = 0; v < V; ++v) s += exp((double)x[v] - m);
+  double l = m + log(s);
+  *tok = arg;
+  *lse = (float)l;
+  *conf = (float)exp(m - l);
+  *gap = (V > 1) ? (float)(m - second) : INFINITY;
+  *rowmax = (float)m;
+}
+
+/* The per-position results at an explicit list of positions.  Rows are
+ * independent, so this is exactly the restriction of the full computation to
+ * those positions; it is how the large workloads are checked on a sample.
+ * H: [T, d] bf16 with row stride ld_h elements.  pos: n positions in [0,T).
+ * Outputs have n entries.  logits_out (may be NULL): n*V fp32, the rows of
+ * logits themselves.  Returns 0, or -1 on a position out of range. */
+int oracle_positions(const uint16_t *H, int64_t T, int32_t d, int64_t ld_h,
+                     const uint16_t *W, int32_t V, const int64_t *pos,
+                     int64_t n, int32_t *tok, float *conf, float *lse,
+                     float *gap, float *rowmax, float *logits_out) {
+  for (int64_t j = 0; j < n; ++j)
+    if (pos[j] < 0 || pos[j] >= T) return -1;
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int64_t j = 0; j < n; ++j) {
+    float *x = logits_out ? logits_out + (size_t)j * (size_t)V
+                          : (float *)malloc(sizeof(float) * (size_t)V);
+    oracle_row_logits(H + (size_t)pos[j] * (size_t)ld_h, W, d, V, x);
+    oracle_row_reduce(x, V, &tok[j], &conf[j], &lse[j], &gap[j], &rowmax[j]);
+    if (!logits_out) free(x);
+  }
+  return 0;
+}
+
+/* The literal statement: results for EVERY position 0..T-1, then keep the
+ * masked ones.  idx/tok/conf/lse/gap/rowmax: room for T entries each; the
+ * first M are written.  Returns M. */
+int64_t oracle_full_then_select(const uint16_t *H, int64_t T, int32_t d,
+                                int64_t ld_h, const uint16_t *W, int32_t V,
+                                const uint8_t *mask, int32_t *idx,
+                                int32_t *tok, float *conf, float *lse,
+                                float *gap, float *rowmax) {
+  if (T <= 0) return 0;
+  int32_t *tok_all = (int32_t *)malloc(sizeof(int32_t) * (size_t)T);
+  float *conf_all = (float *)malloc(sizeof(float) * (size_t)T);
+  float *lse_all = (float *)malloc(sizeof(float) * (size_t)T);
+  float *gap_all = (float *)malloc(sizeof(float) * (size_t)T);
+  float *max_all = (float *)malloc(sizeof(float) * (size_t)T);
+  int64_t *all = (int64_t *)malloc(sizeof(int64_t) * (size_t)T);
+  for (int64_t t = 0; t < T; ++t) all[t] = t;
+  oracle_positions(H, T, d, ld_h, W, V, all, T, tok_all, conf_all, lse_all,
+                   gap_all, max_all, NULL);
+  int64_t M = oracle_mask_select(mask, T, idx);
+  for (int64_t j = 0; j < M; ++j) {
+    int32_t t = idx[j];
+    tok[j] = tok_all[t];
+    conf[j] = conf_all[t];
+    lse[j] = lse_all[t];
+    gap[j] = gap_all[t];
+    rowmax[j] = max_all[t];
+  }
+  free(tok_all); free(conf_all); free(lse_all); free(gap_all); free(max_all);
+  free(all);
+  return M;
+}
+
+/* Number of threads oracle_positions runs on (for the benchmark's report). */
+#ifdef _OPENMP
+#include <omp.h>
+int oracle_num_threads(void) { return omp_get_max_threads(); }
+#else
+int oracle_num_threads(void) { return 1; }
+#endif

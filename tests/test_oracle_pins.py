@@ -1,0 +1,236 @@
+"""Pins for the CPU oracle: every check compares it with something other than itself --
+exact integer brute force, closed forms, invariants and library routines -- chosen so that a
+dropped term, a wrong sign or index, or a transposed operand fails at least one of them.
+The Mosaic paper prints no worked numeric example for this path (it has no tables or
+equations for it), so no paper-quoted values exist to pin against."""
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+from scipy.special import logsumexp, softmax
+
+import oracle
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "closed_forms.txt")
+
+
+def bits(a):
+    """fp32/64 array -> bf16 bit patterns (values must be exactly representable, checked)."""
+    t = torch.as_tensor(np.asarray(a, dtype=np.float32))
+    b = t.to(torch.bfloat16)
+    assert torch.equal(b.float(), t), "test value not representable in bf16"
+    return b.view(torch.uint16).numpy()
+
+
+def rand_bf16(shape, std, seed):
+    g = torch.Generator().manual_seed(seed)
+    return (torch.randn(shape, generator=g) * std).to(torch.bfloat16)
+
+
+# ---------------------------------------------------------------- selection (a1's definition)
+@pytest.mark.parametrize("T", [0, 1, 2, 63, 64, 65, 255, 256, 257, 1000, 4097])
+def test_mask_select_bruteforce(T):
+    rng = np.random.default_rng(T)
+    mask = (rng.random(T) < 0.37).astype(np.uint8) * rng.integers(1, 256, T).astype(np.uint8)
+    want = [t for t in range(T) if mask[t] != 0]
+    got = oracle.mask_select(mask)
+    assert got.dtype == np.int32 and got.tolist() == want
+
+
+def test_mask_select_invariants():
+    T = 5000
+    assert oracle.mask_select(np.ones(T, np.uint8)).tolist() == list(range(T))
+    assert oracle.mask_select(np.zeros(T, np.uint8)).size == 0
+    m = np.zeros(T, np.uint8)
+    m[[0, 255, 256, 4095, 4096, T - 1]] = [1, 2, 128, 255, 7, 1]   # any nonzero byte counts
+    assert oracle.mask_select(m).tolist() == [0, 255, 256, 4095, 4096, T - 1]
+    rng = np.random.default_rng(1)
+    m = (rng.random(T) < 0.5).astype(np.uint8)
+    idx = oracle.mask_select(m)
+    assert np.all(np.diff(idx) > 0) and idx.size == int(m.sum()) and np.all(m[idx] != 0)
+
+
+# ---------------------------------------------------------------- logits: exact integer brute force
+def test_logits_exact_integers_bruteforce():
+    """Small-integer bf16 inputs give integer logits exactly; pure-Python rational arithmetic is the
+    definition.  Asymmetric shapes and values: a transposed operand, a wrong stride or a dropped k
+    changes the result."""
+    rng = np.random.default_rng(7)
+    T, d, V = 5, 12, 9
+    H = rng.integers(-6, 7, (T, d)).astype(np.float32)
+    W = rng.integers(-5, 6, (V, d)).astype(np.float32) * 0.5      # halves are exact in bf16 too
+    Hb, Wb = bits(H), bits(W)
+    for t in range(T):
+        x = oracle.row_logits(Hb[t], Wb)
+        for v in range(V):
+            want = sum(Fraction(float(H[t, k])) * Fraction(float(W[v, k])) for k in range(d))
+            assert Fraction(float(x[v])) == want, (t, v)
+    res, logits = oracle.positions(Hb, Wb, np.arange(T), return_logits=True)
+    for t in range(T):
+        row = [sum(Fraction(float(H[t, k])) * Fraction(float(W[v, k])) for k in range(d)) for v in range(V)]
+        mx = max(row)
+        assert res.tok[t] == row.index(mx)                       # lowest id among maxima
+        assert Fraction(float(res.rowmax[t])) == mx
+        others = [r for i, r in enumerate(row) if i != row.index(mx)]
+        assert Fraction(float(res.gap[t])) == mx - max(others)
+        s = sum(math.exp(float(r - mx)) for r in row)
+        assert res.lse[t] == pytest.approx(float(mx) + math.log(s), abs=1e-6)
+        assert res.conf[t] == pytest.approx(1.0 / s, rel=1e-6)
+
+
+def test_logits_fp64_accumulation_not_fp32():
+    """A sum that fp32 accumulation gets wrong in every order but fp64 gets right:
+    256 + 1/256 + ... : each product is exact, the total needs > 24 bits."""
+    d = 16
+    h = np.ones(d, np.float32)
+    w = np.array([[256.0] + [2.0 ** -18] * (d - 1)], np.float32)
+    x = oracle.row_logits(bits(h), bits(w))
+    exact = 256.0 + (d - 1) * 2.0 ** -18          # = 256.0000572...
+    assert x[0] == np.float32(exact)              # correctly rounded once
+    assert x[0] != np.float32(256.0)              # what step-by-step fp32 adds would give
+
+
+# ---------------------------------------------------------------- library special cases
+def test_logits_vs_torch_fp64_matmul():
+    H = rand_bf16((7, 320), 1.0, 1)
+    W = rand_bf16((513, 320), 320 ** -0.5, 2)
+    want = (H.double() @ W.double().T).numpy()
+    _, logits = oracle.positions(H.view(torch.uint16).numpy(), W.view(torch.uint16).numpy(), np.arange(7),
+                                 return_logits=True)
+    assert np.array_equal(logits, want.astype(np.float32))       # fp64 sum rounded once: same bits
+
+
+def test_reduce_vs_scipy():
+    rng = np.random.default_rng(3)
+    for V, scale in [(1, 1.0), (2, 1.0), (777, 1.0), (8192, 3.0), (5000, 30.0)]:
+        x = (rng.standard_normal(V) * scale).astype(np.float32)
+        tok, conf, lse, gap, mx = oracle.row_reduce(x)
+        xd = x.astype(np.float64)
+        assert tok == int(np.argmax(xd))
+        assert lse == pytest.approx(float(logsumexp(xd)), abs=1e-6 * max(1.0, abs(float(logsumexp(xd)))))
+        assert conf == pytest.approx(float(softmax(xd).max()), rel=2e-6)
+        assert mx == x.max()
+        if V > 1:
+            srt = np.sort(xd)
+            assert gap == pytest.approx(float(srt[-1] - srt[-2]), abs=1e-6)
+        else:
+            assert math.isinf(gap)
+
+
+# ---------------------------------------------------------------- closed forms
+def golden_lnV():
+    out = {}
+    for line in open(GOLDEN):
+        if line.strip() and not line.startswith("#"):
+            v, l = line.split()
+            out[int(v)] = float(l)
+    return out
+
+
+@pytest.mark.parametrize("V", [8192, 126464, 152064])
+def test_constant_row_gives_lnV(V):
+    lnV = golden_lnV()[V]
+    x = np.zeros(V, np.float32)
+    tok, conf, lse, gap, mx = oracle.row_reduce(x)
+    assert tok == 0 and gap == 0.0 and mx == 0.0
+    assert lse == pytest.approx(lnV, abs=2e-6) and conf == pytest.approx(1.0 / V, rel=1e-6)
+    tok, conf, lse, gap, mx = oracle.row_reduce(x + np.float32(-3.25))
+    assert tok == 0 and lse == pytest.approx(-3.25 + lnV, abs=2e-6) and conf == pytest.approx(1.0 / V, rel=1e-6)
+
+
+def test_zero_hidden_row_and_identical_w_rows():
+    V, d = 8192, 64
+    W = rand_bf16((V, d), 0.125, 5).view(torch.uint16).numpy()
+    H = np.zeros((1, d), np.uint16)
+    r = oracle.positions(H, W, [0])
+    assert r.tok[0] == 0 and r.lse[0] == pytest.approx(golden_lnV()[V], abs=2e-6)
+    w_row = rand_bf16((1, d), 0.125, 6)
+    h = rand_bf16((1, d), 1.0, 7)
+    c = float((h.double() @ w_row.double().T).item())
+    Wsame = w_row.repeat(V, 1).view(torch.uint16).numpy()
+    r = oracle.positions(h.view(torch.uint16).numpy(), Wsame, [0])
+    assert r.tok[0] == 0 and r.gap[0] == 0.0
+    assert r.lse[0] == pytest.approx(c + golden_lnV()[V], abs=2e-6 * max(1, abs(c)))
+    assert r.conf[0] == pytest.approx(1.0 / V, rel=1e-6)
+
+
+@pytest.mark.parametrize("vstar", [0, 1, 255, 256, 4095, 8191])
+@pytest.mark.parametrize("a", [2.0, 9.0, 20.0])
+def test_planted_dominant_logit(vstar, a):
+    V, d = 8192, 8
+    H = np.zeros((1, d), np.float32); H[0, 3] = 1.0
+    W = np.zeros((V, d), np.float32); W[vstar, 3] = a
+    W[:, 5] = 7.0                                                 # multiplies a zero of h: must not leak in
+    r = oracle.positions(bits(H), bits(W), [0])
+    s = math.exp(a) + V - 1
+    assert r.tok[0] == vstar and r.rowmax[0] == a and r.gap[0] == pytest.approx(a)
+    assert r.lse[0] == pytest.approx(math.log(s), abs=2e-6)
+    assert r.conf[0] == pytest.approx(math.exp(a) / s, rel=1e-6)
+
+
+@pytest.mark.parametrize("gap", [0.0, 0.0078125, 0.03125])
+def test_two_valued_rows_gap_and_tie(gap):
+    """Top value at ids 5 and (if gap==0) also 3: lowest id must win, gap must be exact."""
+    V = 1000
+    x = np.full(V, -1.0, np.float32)
+    x[5] = 1.0
+    x[3] = 1.0 - gap
+    tok, conf, lse, g, mx = oracle.row_reduce(x)
+    assert tok == (3 if gap == 0.0 else 5)
+    assert g == np.float32(gap)
+    s = 1.0 + math.exp(-gap) + (V - 2) * math.exp(-2.0)
+    assert lse == pytest.approx(1.0 + math.log(s), abs=2e-6) and conf == pytest.approx(1.0 / s, rel=1e-6)
+
+
+# ---------------------------------------------------------------- exact invariances
+def test_power_of_two_scaling_and_row_permutation():
+    H = rand_bf16((3, 128), 1.0, 11)
+    W = rand_bf16((700, 128), 128 ** -0.5, 12)
+    Hb, Wb = H.view(torch.uint16).numpy(), W.view(torch.uint16).numpy()
+    r1, l1 = oracle.positions(Hb, Wb, [0, 1, 2], return_logits=True)
+    r2, l2 = oracle.positions((H * 4).view(torch.uint16).numpy(), Wb, [0, 1, 2], return_logits=True)
+    assert np.array_equal(l2, l1 * 4) and np.array_equal(r1.tok, r2.tok)
+    perm = np.random.default_rng(0).permutation(700)
+    r3, l3 = oracle.positions(Hb, Wb[perm], [0, 1, 2], return_logits=True)
+    assert np.array_equal(l3, l1[:, perm])
+    assert np.array_equal(perm[r3.tok], r1.tok)
+    assert np.allclose(r3.lse, r1.lse, atol=1e-6) and np.allclose(r3.conf, r1.conf, rtol=1e-6)
+
+
+def test_full_then_select_is_restriction_and_independent_of_other_rows():
+    H = rand_bf16((40, 64), 1.0, 21)
+    W = rand_bf16((300, 64), 0.125, 22)
+    Hb, Wb = H.view(torch.uint16).numpy(), W.view(torch.uint16).numpy()
+    rng = np.random.default_rng(2)
+    mask = (rng.random(40) < 0.4).astype(np.uint8)
+    idx, sel = oracle.full_then_select(Hb, Wb, mask)
+    assert idx.tolist() == [t for t in range(40) if mask[t]]
+    allr = oracle.positions(Hb, Wb, np.arange(40))
+    for name in ("tok", "conf", "lse", "gap", "rowmax"):
+        assert np.array_equal(getattr(sel, name), getattr(allr, name)[idx]), name
+    # every selected row equals the direct definition on that row alone (numpy fp64, library matmul)
+    x = (H.double() @ W.double().T).numpy().astype(np.float32).astype(np.float64)
+    assert np.array_equal(sel.tok, x.argmax(1)[idx])
+    assert np.allclose(sel.lse, logsumexp(x, axis=1)[idx], atol=1e-6)
+    # changing unmasked rows changes nothing
+    H2 = H.clone(); H2[torch.from_numpy(mask == 0)] = 0
+    idx2, sel2 = oracle.full_then_select(H2.view(torch.uint16).numpy(), Wb, mask)
+    assert np.array_equal(idx2, idx) and np.array_equal(sel2.lse, sel.lse) and np.array_equal(sel2.tok, sel.tok)
+    # empty and full masks
+    idx0, sel0 = oracle.full_then_select(Hb, Wb, np.zeros(40, np.uint8))
+    assert idx0.size == 0 and sel0.tok.size == 0
+    idx1, sel1 = oracle.full_then_select(Hb, Wb, np.ones(40, np.uint8))
+    assert np.array_equal(idx1, np.arange(40)) and np.array_equal(sel1.lse, allr.lse)
+
+
+def test_statistics_of_gaussian_logits():
+    """Not parity: a sanity check that the tiny workload's logits look like N(0,1) rows, so that
+    E[lse] ~ ln V + 1/2 and the row maximum sits near sqrt(2 ln V)."""
+    from paper_2601_06562_amd import workloads
+    wl = workloads.make("tiny")
+    r = oracle.positions(workloads.bf16_bits(wl.hidden), workloads.bf16_bits(wl.w), np.arange(0, 512, 8))
+    assert abs(float(r.lse.mean()) - (math.log(8192) + 0.5)) < 0.15
+    assert 3.2 < float(r.rowmax.mean()) < 4.6
