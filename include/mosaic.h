@@ -1,0 +1,139 @@
+/*
+ * mosaic.h -- C ABI of libmosaic: the mask-only logits hot path of a diffusion-LLM
+ * denoising step (Mosaic, arXiv 2601.06562), for AMD MI355X (gfx950).
+ *
+ * The path (paper section 2.1 "Diffusion", section 3 observation #2, section 4.2):
+ * a denoising step needs logits only for the positions that are still [MASK]; the
+ * kernel takes the hidden states of ALL positions plus the indices of the masked
+ * ones, gathers rows by indirect addressing while it multiplies by the LM head, and
+ * keeps no gathered copy in global memory.  This library goes one step further than
+ * the paper's kernel: the vocabulary reduction that sampling needs (arg-max id, its
+ * soft-max probability, the row's log-sum-exp) is fused into the GEMM epilogue, so
+ * neither [T,V] nor [M,V] logits ever exist in memory.  Section 4.4's chunking of
+ * the logits operator along the sequence dimension (chunk count K_logits, "lazy":
+ * off unless memory is short, minimal K otherwise) appears as mosaic_plan_workspace.
+ *
+ * Conventions for every call
+ *   - "dev" pointers are device (HBM) pointers owned by the CALLER; "host" pointers
+ *     are ordinary host memory.  The library allocates and frees no device memory
+ *     and keeps no state between calls.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
+ *     only enqueue work on it and return; they never synchronise the device.
+ *   - Return value: MOSAIC_OK (0) or a negative mosaic_status.  On error nothing has
+ *     been enqueued.  mosaic_status_string() names a status.
+ *   - T = flat number of positions (a batch is the concatenation of its sequences,
+ *     no padding -- paper section 5.1), M = number of masked positions, d = hidden
+ *     size, V = vocabulary size.
+ */
+#ifndef MOSAIC_H_
+#define MOSAIC_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  MOSAIC_OK = 0,
+  MOSAIC_ERR_INVALID_ARG = -1,        /* null pointer, negative size, misaligned pointer     */
+  MOSAIC_ERR_UNSUPPORTED_SHAPE = -2,  /* d, ld_h, T or V outside what the kernels handle      */
+  MOSAIC_ERR_WORKSPACE_TOO_SMALL = -3,/* budget / workspace below the non-chunkable minimum   */
+  MOSAIC_ERR_HIP = -4                 /* a HIP runtime call failed (launch, attribute query)  */
+} mosaic_status;
+
+/* Name of a status code; static storage, never NULL. */
+const char *mosaic_status_string(int status);
+
+/* Tile sizes of the fused kernel, exported so callers can size things:
+ * rows of masked tokens per tile, vocabulary ids per tile, and the multiple d must have. */
+#define MOSAIC_ROW_TILE 256
+#define MOSAIC_VOCAB_TILE 256
+#define MOSAIC_K_TILE 64
+#define MOSAIC_MAX_VOCAB_SPLITS 64
+
+/* Result of the chunk-size selector.  All fields are filled by mosaic_plan_workspace;
+ * callers may read them but should not edit them. */
+typedef struct {
+  int64_t workspace_bytes; /* bytes mosaic_masked_logits_reduce needs in `workspace`    */
+  int32_t num_chunks;      /* K_logits: number of sequential chunks over masked rows    */
+  int32_t rows_per_chunk;  /* C: masked rows per chunk, a multiple of MOSAIC_ROW_TILE   */
+  int32_t vocab_splits;    /* S: vocabulary ranges whose partial results are merged     */
+  int32_t tile_panel;      /* row tiles scheduled side by side (cache-sharing group)    */
+  int32_t grid;            /* persistent workgroups launched per chunk                  */
+  int32_t reserved;
+} mosaic_plan;
+
+/*
+ * Chunk-size selector (paper section 4.4, "lazy chunking strategy" and "online
+ * bottleneck-driven search", restricted to the one chunkable operator on this path).
+ * Host-only, pure function.  Starts from K = 1 (chunking off); while the workspace of
+ * one chunk of C = roundup(ceil(max_rows / K), MOSAIC_ROW_TILE) rows exceeds
+ * budget_bytes even with a single vocabulary split, K is raised by one; stops at the
+ * first K that fits (the minimal one) and fails with MOSAIC_ERR_WORKSPACE_TOO_SMALL
+ * when even one row tile with one split does not fit (the non-chunkable floor).
+ * The workspace is 12 * S * C bytes (one (max, sum-exp, arg-max) triple per row and
+ * vocabulary split) -- never O(C * V).
+ *   T          total positions, >= 0, < 2^31
+ *   max_rows   host-side upper bound on M (the search in the paper is driven by the
+ *              number of masks and the number of tokens; pass T if M is unknown), 0..T
+ *   d, V       hidden and vocabulary size; d must be a multiple of MOSAIC_K_TILE
+ *   budget_bytes  <= 0 means unbounded
+ *   num_cus    compute units to schedule for; <= 0 means 256 (one MI355X)
+ *   out_plan   host pointer, written on success
+ */
+int mosaic_plan_workspace(int64_t T, int64_t max_rows, int32_t d, int32_t V, int64_t budget_bytes,
+                          int32_t num_cus, mosaic_plan *out_plan);
+
+/*
+ * Stream compaction of the mask (paper section 4.2: the kernel is handed "mask indices
+ * (identifying masked tokens)"; this call makes them).  Exclusive prefix sum over
+ * mask[t] != 0, then out_idx[scan[t]] = t: the masked positions in ascending order,
+ * bit-exact.  Any nonzero byte counts as masked.
+ *   mask       dev uint8[T]
+ *   out_idx    dev int32[max(T,1)]; the first M entries are written, the rest untouched
+ *   out_count  dev int32[1]; receives M
+ *   scratch    dev, at least mosaic_compact_scratch_bytes(T) bytes, 4-byte aligned
+ * T == 0 is valid (count = 0).  Errors: INVALID_ARG (null pointer, T < 0, scratch too
+ * small), UNSUPPORTED_SHAPE (T >= 2^31), HIP.
+ */
+int64_t mosaic_compact_scratch_bytes(int64_t T);
+int mosaic_mask_compact(const uint8_t *mask, int64_t T, int32_t *out_idx, int32_t *out_count, void *scratch,
+                        int64_t scratch_bytes, void *stream);
+
+/*
+ * Mask-only logits with the vocabulary reduction fused in (paper section 4.2 for the
+ * gather-GEMM; the reduction is this library's reading of section 2.1's "tokens are
+ * sampled from the logits": greedy).  For every j < *count, with t = idx[j]:
+ *   x[v]        = sum_k hidden[t,k] * w[v,k]      bf16 x bf16, fp32 accumulation, no bias
+ *   out_token[j] = lowest v attaining max_v x[v]
+ *   out_lse[j]   = log sum_v exp(x[v])
+ *   out_conf[j]  = exp(max_v x[v] - out_lse[j])   (soft-max probability of out_token[j])
+ * Rows are processed in plan->num_chunks sequential chunks of plan->rows_per_chunk.
+ *   hidden     dev bf16[T, d], row-major, row stride ld_h elements (ld_h >= d,
+ *              ld_h % 8 == 0), 16-byte aligned; only rows named by idx are read
+ *   w          dev bf16[V, d], row-major, dense, 16-byte aligned
+ *   idx        dev int32[>= *count], every entry in [0, T) (as mosaic_mask_compact makes)
+ *   count      dev int32[1], read on the device: 0 <= *count <= max_rows.  If it exceeds
+ *              max_rows only the first max_rows rows are produced.
+ *   max_rows   the bound the plan was made for
+ *   out_*      dev, max_rows entries each; entries >= *count are left untouched
+ *   plan       host pointer, from mosaic_plan_workspace with the same T, max_rows, d, V
+ *   workspace  dev, >= plan->workspace_bytes, 16-byte aligned; contents are scratch
+ * max_rows == 0 or V == 0 enqueue nothing.  Inputs must be finite; a NaN or Inf in a
+ * row gives unspecified values for that row only.  Errors: INVALID_ARG,
+ * UNSUPPORTED_SHAPE (d % MOSAIC_K_TILE, ld_h, T >= 2^31, V >= 2^31 - 256),
+ * WORKSPACE_TOO_SMALL, HIP.
+ */
+int mosaic_masked_logits_reduce(const void *hidden, int64_t T, int32_t d, int64_t ld_h, const void *w, int32_t V,
+                                const int32_t *idx, const int32_t *count, int64_t max_rows, int32_t *out_token,
+                                float *out_conf, float *out_lse, const mosaic_plan *plan, void *workspace,
+                                int64_t workspace_bytes, void *stream);
+
+/* Library version, "major.minor" as major*1000 + minor. */
+int mosaic_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOSAIC_H_ */

@@ -1,0 +1,180 @@
+"""ctypes binding of libmosaic.so -- argument marshalling only.
+
+Every step of the path runs in the HIP kernels behind the C ABI declared in
+``include/mosaic.h``; the functions here have the same names and only turn torch tensors
+into device pointers.  There is no CPU or PyTorch fallback: if the library is missing,
+loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libmosaic.so")
+
+MOSAIC_OK = 0
+MOSAIC_ERR_INVALID_ARG = -1
+MOSAIC_ERR_UNSUPPORTED_SHAPE = -2
+MOSAIC_ERR_WORKSPACE_TOO_SMALL = -3
+MOSAIC_ERR_HIP = -4
+ROW_TILE = 256
+VOCAB_TILE = 256
+K_TILE = 64
+
+EXPORTS = (
+    "mosaic_status_string", "mosaic_plan_workspace", "mosaic_compact_scratch_bytes", "mosaic_mask_compact",
+    "mosaic_masked_logits_reduce", "mosaic_version",
+)
+
+
+class MosaicPlan(ctypes.Structure):
+    _fields_ = [
+        ("workspace_bytes", ctypes.c_int64),
+        ("num_chunks", ctypes.c_int32),
+        ("rows_per_chunk", ctypes.c_int32),
+        ("vocab_splits", ctypes.c_int32),
+        ("tile_panel", ctypes.c_int32),
+        ("grid", ctypes.c_int32),
+        ("reserved", ctypes.c_int32),
+    ]
+
+    def __repr__(self):
+        return ("MosaicPlan(workspace_bytes=%d, num_chunks=%d, rows_per_chunk=%d, vocab_splits=%d, tile_panel=%d, "
+                "grid=%d)" % (self.workspace_bytes, self.num_chunks, self.rows_per_chunk, self.vocab_splits,
+                              self.tile_panel, self.grid))
+
+
+class MosaicError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} ({status})")
+
+
+_lib = None
+
+
+def lib():
+    """The loaded libmosaic.so.  Raises if it has not been built (run __graft_entry__.build())."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} is missing: build it with `python -m paper_2601_06562_amd.build` "
+                                    "(there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        p, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32
+        L.mosaic_status_string.restype = ctypes.c_char_p
+        L.mosaic_status_string.argtypes = [ctypes.c_int]
+        L.mosaic_version.restype = ctypes.c_int
+        L.mosaic_version.argtypes = []
+        L.mosaic_plan_workspace.restype = ctypes.c_int
+        L.mosaic_plan_workspace.argtypes = [i64, i64, i32, i32, i64, i32, ctypes.POINTER(MosaicPlan)]
+        L.mosaic_compact_scratch_bytes.restype = i64
+        L.mosaic_compact_scratch_bytes.argtypes = [i64]
+        L.mosaic_mask_compact.restype = ctypes.c_int
+        L.mosaic_mask_compact.argtypes = [p, i64, p, p, p, i64, p]
+        L.mosaic_masked_logits_reduce.restype = ctypes.c_int
+        L.mosaic_masked_logits_reduce.argtypes = [p, i64, i32, i64, p, i32, p, p, i64, p, p, p,
+                                                  ctypes.POINTER(MosaicPlan), p, i64, p]
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().mosaic_status_string(int(status)).decode()
+
+
+def _check(status, where):
+    if status != MOSAIC_OK:
+        raise MosaicError(status, where)
+
+
+def _stream_ptr(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _dev_ptr(t, name, dtype=None):
+    if t is None:
+        return ctypes.c_void_p(0)
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live in device memory")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"{name} must be {dtype}, got {t.dtype}")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def mosaic_plan_workspace(T, max_rows, d, V, budget_bytes=0, num_cus=0) -> MosaicPlan:
+    plan = MosaicPlan()
+    _check(lib().mosaic_plan_workspace(T, max_rows, d, V, budget_bytes, num_cus, ctypes.byref(plan)),
+           "mosaic_plan_workspace")
+    return plan
+
+
+def mosaic_compact_scratch_bytes(T) -> int:
+    return int(lib().mosaic_compact_scratch_bytes(T))
+
+
+def mosaic_mask_compact(mask, out_idx, out_count, scratch, stream=None):
+    """mask uint8[T] -> out_idx int32[>=max(T,1)] (first M written), out_count int32[1]; all device tensors."""
+    T = mask.numel()
+    if T and not mask.is_contiguous():
+        raise ValueError("mask must be contiguous")
+    _check(lib().mosaic_mask_compact(_dev_ptr(mask, "mask", torch.uint8) if T else ctypes.c_void_p(0), T,
+                                     _dev_ptr(out_idx, "out_idx", torch.int32),
+                                     _dev_ptr(out_count, "out_count", torch.int32), _dev_ptr(scratch, "scratch"),
+                                     scratch.numel() * scratch.element_size(), _stream_ptr(stream)),
+           "mosaic_mask_compact")
+
+
+def mosaic_masked_logits_reduce(hidden, w, idx, count, max_rows, out_token, out_conf, out_lse, plan, workspace,
+                                stream=None):
+    """hidden bf16[T,d] (row stride >= d), w bf16[V,d], idx int32, count int32[1] -> out_* (device tensors)."""
+    T, d = hidden.shape
+    V, d2 = w.shape
+    if d != d2:
+        raise ValueError("hidden and w disagree on d")
+    if hidden.stride(1) != 1 or not w.is_contiguous():
+        raise ValueError("hidden rows and w must be dense along d")
+    ld_h = hidden.stride(0) if T > 1 else d
+    _check(lib().mosaic_masked_logits_reduce(
+        _dev_ptr(hidden, "hidden", torch.bfloat16), T, d, ld_h, _dev_ptr(w, "w", torch.bfloat16), V,
+        _dev_ptr(idx, "idx", torch.int32), _dev_ptr(count, "count", torch.int32), max_rows,
+        _dev_ptr(out_token, "out_token", torch.int32), _dev_ptr(out_conf, "out_conf", torch.float32),
+        _dev_ptr(out_lse, "out_lse", torch.float32), ctypes.byref(plan), _dev_ptr(workspace, "workspace"),
+        workspace.numel() * workspace.element_size() if workspace is not None else 0, _stream_ptr(stream)),
+        "mosaic_masked_logits_reduce")
+
+
+class MaskOnlyLogits:
+    """Caller-side buffers for one shape, reused across denoising steps: the index list, the count, the
+    scan scratch, the partials workspace and the three outputs.  `step` enqueues compaction + the fused
+    reduction on the current stream and returns views; it never synchronises."""
+
+    def __init__(self, T, d, V, max_rows=None, budget_bytes=0, device="cuda"):
+        self.T, self.d, self.V = T, d, V
+        self.max_rows = T if max_rows is None else max_rows
+        self.plan = mosaic_plan_workspace(T, self.max_rows, d, V, budget_bytes)
+        dev = torch.device(device)
+        self.idx = torch.empty(max(T, 1), dtype=torch.int32, device=dev)
+        self.count = torch.zeros(1, dtype=torch.int32, device=dev)
+        self.scratch = torch.empty(max(mosaic_compact_scratch_bytes(T), 16), dtype=torch.uint8, device=dev)
+        self.workspace = torch.empty(max(self.plan.workspace_bytes, 16), dtype=torch.uint8, device=dev)
+        n = max(self.max_rows, 1)
+        self.token = torch.empty(n, dtype=torch.int32, device=dev)
+        self.conf = torch.empty(n, dtype=torch.float32, device=dev)
+        self.lse = torch.empty(n, dtype=torch.float32, device=dev)
+
+    @property
+    def workspace_bytes(self) -> int:
+        """Every device byte the path holds beyond its inputs and its three outputs."""
+        return (self.idx.numel() * 4 + 4 + self.scratch.numel() + self.workspace.numel())
+
+    def step(self, hidden, w, mask, stream=None):
+        mosaic_mask_compact(mask, self.idx, self.count, self.scratch, stream)
+        mosaic_masked_logits_reduce(hidden, w, self.idx, self.count, self.max_rows, self.token, self.conf, self.lse,
+                                    self.plan, self.workspace, stream)
+        return self.idx, self.count, self.token, self.conf, self.lse

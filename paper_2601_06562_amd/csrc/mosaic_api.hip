@@ -1,0 +1,81 @@
+// C ABI entry points of libmosaic: argument validation, then enqueue.  See include/mosaic.h.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "mosaic_internal.h"
+
+extern "C" {
+
+const char* mosaic_status_string(int status) {
+  switch (status) {
+    case MOSAIC_OK: return "MOSAIC_OK";
+    case MOSAIC_ERR_INVALID_ARG: return "MOSAIC_ERR_INVALID_ARG";
+    case MOSAIC_ERR_UNSUPPORTED_SHAPE: return "MOSAIC_ERR_UNSUPPORTED_SHAPE";
+    case MOSAIC_ERR_WORKSPACE_TOO_SMALL: return "MOSAIC_ERR_WORKSPACE_TOO_SMALL";
+    case MOSAIC_ERR_HIP: return "MOSAIC_ERR_HIP";
+    default: return "MOSAIC_ERR_UNKNOWN";
+  }
+}
+
+int mosaic_version(void) { return 1000; }
+
+int64_t mosaic_compact_scratch_bytes(int64_t T) {
+  if (T < 0) return 0;
+  return 4 * (mosaic::compact_num_blocks(T) + 4);
+}
+
+int mosaic_mask_compact(const uint8_t* mask, int64_t T, int32_t* out_idx, int32_t* out_count, void* scratch,
+                        int64_t scratch_bytes, void* stream) {
+  if (T < 0 || out_idx == nullptr || out_count == nullptr || scratch == nullptr || (T > 0 && mask == nullptr))
+    return MOSAIC_ERR_INVALID_ARG;
+  if (T >= (int64_t)1 << 31) return MOSAIC_ERR_UNSUPPORTED_SHAPE;
+  if (scratch_bytes < mosaic_compact_scratch_bytes(T) || (reinterpret_cast<uintptr_t>(scratch) & 3u) != 0)
+    return MOSAIC_ERR_INVALID_ARG;
+  const int rc = mosaic::launch_compact(mask, T, out_idx, out_count, static_cast<int32_t*>(scratch),
+                                        static_cast<hipStream_t>(stream));
+  return rc == 0 ? MOSAIC_OK : MOSAIC_ERR_HIP;
+}
+
+int mosaic_masked_logits_reduce(const void* hidden, int64_t T, int32_t d, int64_t ld_h, const void* w, int32_t V,
+                                const int32_t* idx, const int32_t* count, int64_t max_rows, int32_t* out_token,
+                                float* out_conf, float* out_lse, const mosaic_plan* plan, void* workspace,
+                                int64_t workspace_bytes, void* stream) {
+  if (T < 0 || d <= 0 || V < 0 || max_rows < 0 || max_rows > T || plan == nullptr || count == nullptr)
+    return MOSAIC_ERR_INVALID_ARG;
+  if (T >= (int64_t)1 << 31 || (int64_t)V >= ((int64_t)1 << 31) - MOSAIC_VOCAB_TILE || d % MOSAIC_K_TILE != 0 ||
+      ld_h < d || ld_h % 8 != 0)
+    return MOSAIC_ERR_UNSUPPORTED_SHAPE;
+  if (max_rows == 0 || V == 0) return MOSAIC_OK;
+  if (hidden == nullptr || w == nullptr || idx == nullptr || out_token == nullptr || out_conf == nullptr ||
+      out_lse == nullptr || workspace == nullptr)
+    return MOSAIC_ERR_INVALID_ARG;
+  if ((reinterpret_cast<uintptr_t>(hidden) & 15u) || (reinterpret_cast<uintptr_t>(w) & 15u) ||
+      (reinterpret_cast<uintptr_t>(workspace) & 15u))
+    return MOSAIC_ERR_INVALID_ARG;
+  // The plan must be one the selector could have produced for these sizes.
+  const int64_t vocab_tiles = ((int64_t)V + MOSAIC_VOCAB_TILE - 1) / MOSAIC_VOCAB_TILE;
+  if (plan->num_chunks < 1 || plan->rows_per_chunk < MOSAIC_ROW_TILE || plan->rows_per_chunk % MOSAIC_ROW_TILE != 0 ||
+      plan->vocab_splits < 1 || plan->vocab_splits > MOSAIC_MAX_VOCAB_SPLITS || plan->vocab_splits > vocab_tiles ||
+      plan->tile_panel < 1 || plan->grid < 1 || (int64_t)plan->num_chunks * plan->rows_per_chunk < max_rows)
+    return MOSAIC_ERR_INVALID_ARG;
+  const int64_t need = mosaic::partials_bytes(plan->rows_per_chunk, plan->vocab_splits);
+  if (plan->workspace_bytes < need || workspace_bytes < need) return MOSAIC_ERR_WORKSPACE_TOO_SMALL;
+
+  mosaic::LogitsArgs a;
+  a.hidden = hidden;
+  a.ld_h = ld_h;
+  a.w = w;
+  a.d = d;
+  a.V = V;
+  a.idx = idx;
+  a.count = count;
+  a.max_rows = max_rows;
+  a.out_token = out_token;
+  a.out_conf = out_conf;
+  a.out_lse = out_lse;
+  a.workspace = workspace;
+  const int rc = mosaic::launch_masked_logits(a, *plan, static_cast<hipStream_t>(stream));
+  return rc == 0 ? MOSAIC_OK : MOSAIC_ERR_HIP;
+}
+
+}  // extern "C"

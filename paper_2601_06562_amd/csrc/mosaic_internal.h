@@ -1,0 +1,39 @@
+// Internal declarations shared by the translation units of libmosaic (not part of the C ABI).
+#ifndef MOSAIC_INTERNAL_H_
+#define MOSAIC_INTERNAL_H_
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "mosaic.h"
+
+namespace mosaic {
+
+// ---- mask compaction (mosaic_compact.hip)
+int64_t compact_num_blocks(int64_t T);
+int launch_compact(const uint8_t* mask, int64_t T, int32_t* out_idx, int32_t* out_count, int32_t* block_counts,
+                   hipStream_t stream);
+
+// ---- fused gather-GEMM + vocabulary reduction (mosaic_logits.hip)
+struct LogitsArgs {
+  const void* hidden;   // bf16 [T, ld_h]
+  int64_t ld_h;         // elements
+  const void* w;        // bf16 [V, d]
+  int32_t d;
+  int32_t V;
+  const int32_t* idx;   // masked positions, ascending
+  const int32_t* count; // device scalar M
+  int64_t max_rows;
+  int32_t* out_token;
+  float* out_conf;
+  float* out_lse;
+  void* workspace;
+};
+int launch_masked_logits(const LogitsArgs& a, const mosaic_plan& plan, hipStream_t stream);
+
+// ---- host-side selector (mosaic_plan.cpp)
+int32_t choose_vocab_splits(int64_t row_tiles, int64_t vocab_tiles, int32_t num_cus);
+int64_t partials_bytes(int64_t rows_padded, int32_t splits);
+
+}  // namespace mosaic
+#endif

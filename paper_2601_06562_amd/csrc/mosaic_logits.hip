@@ -1,0 +1,403 @@
+// Fused gather-GEMM + vocabulary reduction for mask-only logits on gfx950 (MI355X).
+//
+// Paper section 4.2 describes a gather-GEMM: the kernel gets the hidden states of all positions
+// plus the indices of the masked ones, computes row addresses by pointer arithmetic, stages the
+// scattered rows in on-chip memory, multiplies, accumulates, and discards each tile -- no gathered
+// copy in global memory.  This kernel keeps that idea (the gather is folded into the global->LDS
+// copy, one address per lane) and, unlike the paper's kernel, never writes logits either: every
+// 256x256 tile of logits lives only in MFMA accumulators and is reduced on the spot to a running
+// (max, sum-exp, arg-max) per token row.
+//
+// Shape of the computation.  The MFMA "A" operand is the LM-head tile (vocabulary ids along the
+// instruction's rows), "B" is the gathered hidden tile (token rows along the instruction's columns).
+// With v_mfma_f32_32x32x16_bf16 a lane then owns ONE token (column lane%32) and 16 vocabulary ids of a
+// 32x32 block, so the reduction over the vocabulary is almost entirely in-register; the only
+// cross-lane step (lane ^ 32) and the cross-wave step happen once per work unit, not per tile.
+//
+// Work decomposition.  A unit is (row tile of 256 masked tokens, vocabulary split); a workgroup of
+// 8 waves walks the 256-wide vocabulary tiles of its split, carrying the running triple in registers,
+// and writes one partial triple per row at the end.  A second tiny kernel merges the S partials per
+// row in fixed order (deterministic) and emits token, confidence and log-sum-exp.
+//
+// Data movement.  Global->LDS copies use the direct-to-LDS 16-byte loads of gfx950; both tiles are
+// K-contiguous ([256 rows][64 k] bf16 = 128 B per row) and 16-byte chunks are XOR-swizzled by row so
+// that the ds_read_b128 operand fetches of 32 consecutive rows spread over all LDS banks.  A ring of
+// stages is filled one K-tile ahead; one workgroup barrier per K-tile.
+#include <hip/hip_runtime.h>
+#include <limits.h>
+#include <stdint.h>
+#include <stdlib.h>
+
+#include "mosaic_internal.h"
+
+namespace mosaic {
+
+using bf16x8 = __attribute__((ext_vector_type(8))) __bf16;
+using f32x16 = __attribute__((ext_vector_type(16))) float;
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+typedef const __attribute__((address_space(1))) void* gbl_ptr_t;
+
+constexpr int kTileRows = MOSAIC_ROW_TILE;     // masked tokens per tile (MFMA N side)
+constexpr int kTileVocab = MOSAIC_VOCAB_TILE;  // vocabulary ids per tile (MFMA M side)
+constexpr int kTileK = MOSAIC_K_TILE;          // 64 bf16 = 128 bytes per row per stage
+constexpr int kThreads = 512;                  // 8 waves: 2 (vocabulary halves) x 4 (token quarters)
+constexpr int kRowBytes = kTileK * 2;
+constexpr int kOperandBytes = 256 * kRowBytes;       // 32 KiB per operand tile
+constexpr int kStageBytes = 2 * kOperandBytes;       // W tile then H tile
+constexpr int kLoadsPerStage = 8;                    // direct-to-LDS instructions per wave per stage
+constexpr float kNeg = -1.0e30f;                     // "minus infinity" that survives subtraction
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+struct KernelParams {
+  const char* hidden;
+  int64_t ldh_bytes;
+  const char* w;
+  int32_t d;
+  int32_t V;
+  const int32_t* idx;
+  const int32_t* count;
+  int32_t row0;        // first compacted row of this chunk
+  int32_t chunk_rows;  // capacity of the chunk (C)
+  int32_t max_rows;
+  int32_t splits;      // S
+  int32_t panel;       // row tiles scheduled side by side
+  int32_t vocab_tiles; // ceil(V / 256)
+  int32_t c_pad;       // row capacity of the partial arrays
+  float* part_m;
+  float* part_s;
+  int32_t* part_i;
+  int32_t* out_token;
+  float* out_conf;
+  float* out_lse;
+};
+
+// (m, s, i) monoid: max, sum of exp relative to the max, lowest index attaining the max.
+__device__ __forceinline__ void merge_triple(float& m, float& s, int& i, float m2, float s2, int i2) {
+  const float mn = fmaxf(m, m2);
+  const float a = __builtin_amdgcn_exp2f((m - mn) * kLog2e);
+  const float b = __builtin_amdgcn_exp2f((m2 - mn) * kLog2e);
+  const bool keep = (m > m2) || (m == m2 && i < i2);
+  s = s * a + s2 * b;
+  i = keep ? i : i2;
+  m = mn;
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vm() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// Wait until at most `tiles_after` later stages (8 loads each) are still in flight.
+template <int NST>
+__device__ __forceinline__ void wait_stage(int tiles_after) {
+  if constexpr (NST <= 2) {
+    wait_vm<0>();
+  } else if constexpr (NST == 3) {
+    if (tiles_after >= 1) wait_vm<kLoadsPerStage>(); else wait_vm<0>();
+  } else {
+    if (tiles_after >= 2) wait_vm<2 * kLoadsPerStage>();
+    else if (tiles_after == 1) wait_vm<kLoadsPerStage>();
+    else wait_vm<0>();
+  }
+}
+
+// Reduce one finished 256x256 logits tile (this wave's 128 vocabulary ids x 64 tokens) into the
+// lane's running triples.  vb = vocabulary id of this lane's element (block 0, register 0).
+template <bool TAIL>
+__device__ __forceinline__ void reduce_tile(f32x16 (&acc)[4][2], float (&m)[2], float (&s)[2], int (&ix)[2], int vb,
+                                            int V) {
+#pragma unroll
+  for (int bj = 0; bj < 2; ++bj) {
+    float mt = kNeg;
+#pragma unroll
+    for (int bi = 0; bi < 4; ++bi) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int code = bi * 32 + 8 * (r >> 2) + (r & 3);
+        if (TAIL) {
+          if (vb + code >= V) acc[bi][bj][r] = kNeg;
+        }
+        mt = fmaxf(mt, acc[bi][bj][r]);
+      }
+    }
+    int sel = 0;
+#pragma unroll
+    for (int bi = 3; bi >= 0; --bi) {
+#pragma unroll
+      for (int r = 15; r >= 0; --r) {
+        const int code = bi * 32 + 8 * (r >> 2) + (r & 3);
+        sel = (acc[bi][bj][r] == mt) ? code : sel;  // descending scan: the lowest id wins
+      }
+    }
+    const bool upd = mt > m[bj];  // strict: an equal maximum in a later tile has a higher id
+    ix[bj] = upd ? vb + sel : ix[bj];
+    const float mn = fmaxf(m[bj], mt);
+    const float nml = -mn * kLog2e;
+    float p0 = 0.f, p1 = 0.f, p2 = 0.f, p3 = 0.f;
+#pragma unroll
+    for (int bi = 0; bi < 4; ++bi) {
+#pragma unroll
+      for (int r = 0; r < 16; r += 4) {
+        p0 += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[bi][bj][r + 0], kLog2e, nml));
+        p1 += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[bi][bj][r + 1], kLog2e, nml));
+        p2 += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[bi][bj][r + 2], kLog2e, nml));
+        p3 += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[bi][bj][r + 3], kLog2e, nml));
+      }
+    }
+    s[bj] = s[bj] * __builtin_amdgcn_exp2f((m[bj] - mn) * kLog2e) + ((p0 + p1) + (p2 + p3));
+    m[bj] = mn;
+  }
+}
+
+template <int NST, int SWZ>
+__global__ __launch_bounds__(kThreads) void masked_logits_kernel(const KernelParams p) {
+  constexpr int kRing = NST * kStageBytes;
+  __shared__ __attribute__((aligned(1024))) char smem[kRing + 3 * 256 * 4];
+  float* red_m = reinterpret_cast<float*>(smem + kRing);
+  float* red_s = red_m + 256;
+  int* red_i = reinterpret_cast<int*>(red_s + 256);
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wv = wave & 1;   // vocabulary half of the tile
+  const int wt = wave >> 1;  // token quarter of the tile
+  const int l32 = lane & 31, lhalf = lane >> 5;
+
+  int total = *p.count;
+  if (total > p.max_rows) total = p.max_rows;
+  int rows = total - p.row0;
+  if (rows > p.chunk_rows) rows = p.chunk_rows;
+  if (rows <= 0) return;
+  const int n_tt = (rows + kTileRows - 1) / kTileRows;
+
+  // Position in the schedule.  Workgroups are dealt round-robin to the 8 XCDs, so workgroups
+  // b, b+8, b+16, ... share an L2: give them consecutive units.
+  const int G = gridDim.x;
+  int pos = blockIdx.x;
+  if ((G & 7) == 0) pos = (int)(blockIdx.x & 7) * (G >> 3) + (int)(blockIdx.x >> 3);
+  const int S = p.splits;
+  const int n_units = n_tt * S;
+  const int A = p.panel < n_tt ? p.panel : n_tt;
+  const int full_panel_units = A * S;
+  const int n_panels = (n_tt + A - 1) / A;
+
+  // Direct-to-LDS copy: instruction i of this wave fills rows wave*32 + 8*i + lane/8 of a tile,
+  // lane%8 is the physical 16-byte chunk; the logical chunk fetched there is swizzled by the row.
+  const int drow = wave * 32 + (lane >> 3);
+  int src_chunk_bytes[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) src_chunk_bytes[i] = (((lane & 7) ^ (((drow + 8 * i) >> SWZ) & 7))) * 16;
+
+  // MFMA operand fetch: row = 32-row block base + lane%32, logical chunk 2*ks + lane/32.
+  int rd_off[4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) rd_off[ks] = l32 * kRowBytes + (((2 * ks + lhalf) ^ ((l32 >> SWZ) & 7)) * 16);
+
+  const int nk = p.d / kTileK;
+
+  for (int u = pos; u < n_units; u += G) {
+    int pnl = u / full_panel_units;
+    if (pnl >= n_panels) pnl = n_panels - 1;
+    const int ul = u - pnl * full_panel_units;
+    const int hp = (n_tt - pnl * A) < A ? (n_tt - pnl * A) : A;
+    const int sp = ul / hp;
+    const int tt = pnl * A + ul % hp;
+    const int vt0 = (int)(((int64_t)sp * p.vocab_tiles) / S);
+    const int vt1 = (int)(((int64_t)(sp + 1) * p.vocab_tiles) / S);
+    const int ntile = vt1 - vt0;
+    const int total_steps = ntile * nk;
+
+    // Gather: per-lane base pointers of the 4 hidden rows this lane copies.  Rows past the end of
+    // the chunk re-read the last valid row; their results are never stored.
+    const char* hptr[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      int j = tt * kTileRows + drow + 8 * i;
+      if (j > rows - 1) j = rows - 1;
+      const int t = p.idx[p.row0 + j];
+      hptr[i] = p.hidden + (int64_t)t * p.ldh_bytes + src_chunk_bytes[i];
+    }
+    const char* wptr[4];
+
+    int ld_vt = vt0, ld_k = 0, ld_stage = 0, ld_issued = 0;
+    auto issue = [&]() {
+      if (ld_k == 0) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          int v = ld_vt * kTileVocab + drow + 8 * i;
+          if (v > p.V - 1) v = p.V - 1;  // tail tile: clamp, masked in the reduction
+          wptr[i] = p.w + (int64_t)v * ((int64_t)p.d * 2) + src_chunk_bytes[i];
+        }
+      }
+      char* stage = smem + ld_stage * kStageBytes + (wave * 32) * kRowBytes;
+      const int koff = ld_k * kRowBytes;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        __builtin_amdgcn_global_load_lds((gbl_ptr_t)(wptr[i] + koff), (lds_ptr_t)(stage + i * 8 * kRowBytes), 16, 0, 0);
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        __builtin_amdgcn_global_load_lds((gbl_ptr_t)(hptr[i] + koff),
+                                         (lds_ptr_t)(stage + kOperandBytes + i * 8 * kRowBytes), 16, 0, 0);
+      ld_k += 1;
+      if (ld_k == nk) {
+        ld_k = 0;
+        ld_vt += 1;
+      }
+      ld_stage = (ld_stage + 1 == NST) ? 0 : ld_stage + 1;
+      ld_issued += 1;
+    };
+
+    float run_m[2] = {kNeg, kNeg};
+    float run_s[2] = {0.f, 0.f};
+    int run_i[2] = {INT_MAX, INT_MAX};
+
+    wait_vm<0>();
+#pragma unroll
+    for (int q = 0; q < NST - 1; ++q)
+      if (ld_issued < total_steps) issue();
+
+    int st = 0, step = 0;
+    for (int n = 0; n < ntile; ++n) {
+      f32x16 acc[4][2];
+#pragma unroll
+      for (int bi = 0; bi < 4; ++bi)
+#pragma unroll
+        for (int bj = 0; bj < 2; ++bj)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc[bi][bj][r] = 0.f;
+
+      for (int kt = 0; kt < nk; ++kt, ++step) {
+        wait_stage<NST>(ld_issued - step - 1);
+        __builtin_amdgcn_s_barrier();  // stage `st` is complete for every wave; stage st-1 is free
+        if (ld_issued < total_steps) issue();
+
+        const char* wbase = smem + st * kStageBytes + (wv * 128) * kRowBytes;
+        const char* hbase = smem + st * kStageBytes + kOperandBytes + (wt * 64) * kRowBytes;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+          bf16x8 a[4], b[2];
+#pragma unroll
+          for (int bi = 0; bi < 4; ++bi) a[bi] = *reinterpret_cast<const bf16x8*>(wbase + bi * 32 * kRowBytes + rd_off[ks]);
+#pragma unroll
+          for (int bj = 0; bj < 2; ++bj) b[bj] = *reinterpret_cast<const bf16x8*>(hbase + bj * 32 * kRowBytes + rd_off[ks]);
+#pragma unroll
+          for (int bi = 0; bi < 4; ++bi)
+#pragma unroll
+            for (int bj = 0; bj < 2; ++bj)
+              acc[bi][bj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[bi], b[bj], acc[bi][bj], 0, 0, 0);
+        }
+        st = (st + 1 == NST) ? 0 : st + 1;
+      }
+
+      const int v_tile0 = (vt0 + n) * kTileVocab;
+      const int vb = v_tile0 + wv * 128 + 4 * lhalf;
+      if (v_tile0 + kTileVocab > p.V) reduce_tile<true>(acc, run_m, run_s, run_i, vb, p.V);
+      else reduce_tile<false>(acc, run_m, run_s, run_i, vb, p.V);
+    }
+
+    // Unit end: fold the two lanes that share a token (lane ^ 32), then the two waves that share
+    // it (vocabulary halves) through LDS, and publish one partial triple per row.
+#pragma unroll
+    for (int bj = 0; bj < 2; ++bj) {
+      const float m2 = __shfl_xor(run_m[bj], 32, 64);
+      const float s2 = __shfl_xor(run_s[bj], 32, 64);
+      const int i2 = __shfl_xor(run_i[bj], 32, 64);
+      merge_triple(run_m[bj], run_s[bj], run_i[bj], m2, s2, i2);
+    }
+    if (wv == 1 && lhalf == 0) {
+#pragma unroll
+      for (int bj = 0; bj < 2; ++bj) {
+        const int e = (wt * 2 + bj) * 32 + l32;
+        red_m[e] = run_m[bj];
+        red_s[e] = run_s[bj];
+        red_i[e] = run_i[bj];
+      }
+    }
+    __syncthreads();  // also: every wave is done with the ring before the next unit refills it
+    if (wv == 0 && lhalf == 0) {
+#pragma unroll
+      for (int bj = 0; bj < 2; ++bj) {
+        const int e = (wt * 2 + bj) * 32 + l32;
+        merge_triple(run_m[bj], run_s[bj], run_i[bj], red_m[e], red_s[e], red_i[e]);
+        const int64_t slot = (int64_t)sp * p.c_pad + tt * kTileRows + e;
+        p.part_m[slot] = run_m[bj];
+        p.part_s[slot] = run_s[bj];
+        p.part_i[slot] = run_i[bj];
+      }
+    }
+  }
+}
+
+// Merge the S partial triples of every row in ascending split order and emit the outputs.
+__global__ __launch_bounds__(256) void combine_kernel(const KernelParams p) {
+  int total = *p.count;
+  if (total > p.max_rows) total = p.max_rows;
+  int rows = total - p.row0;
+  if (rows > p.chunk_rows) rows = p.chunk_rows;
+  const int r = blockIdx.x * 256 + threadIdx.x;
+  if (r >= rows) return;
+  float m = kNeg, s = 0.f;
+  int i = INT_MAX;
+  for (int sp = 0; sp < p.splits; ++sp) {
+    const int64_t slot = (int64_t)sp * p.c_pad + r;
+    merge_triple(m, s, i, p.part_m[slot], p.part_s[slot], p.part_i[slot]);
+  }
+  p.out_token[p.row0 + r] = i;
+  p.out_lse[p.row0 + r] = m + __builtin_amdgcn_logf(s) * kLn2;
+  p.out_conf[p.row0 + r] = 1.0f / s;
+}
+
+static int variant_from_env() {
+  const char* e = getenv("MOSAIC_KERNEL_VARIANT");
+  return e ? atoi(e) : 0;
+}
+
+int launch_masked_logits(const LogitsArgs& a, const mosaic_plan& plan, hipStream_t stream) {
+  static const int variant = variant_from_env();
+  KernelParams p;
+  p.hidden = static_cast<const char*>(a.hidden);
+  p.ldh_bytes = a.ld_h * 2;
+  p.w = static_cast<const char*>(a.w);
+  p.d = a.d;
+  p.V = a.V;
+  p.idx = a.idx;
+  p.count = a.count;
+  p.chunk_rows = plan.rows_per_chunk;
+  p.max_rows = (int32_t)a.max_rows;
+  p.splits = plan.vocab_splits;
+  p.panel = plan.tile_panel;
+  p.vocab_tiles = (a.V + kTileVocab - 1) / kTileVocab;
+  p.c_pad = plan.rows_per_chunk;
+  p.part_m = static_cast<float*>(a.workspace);
+  p.part_s = p.part_m + (int64_t)plan.vocab_splits * plan.rows_per_chunk;
+  p.part_i = reinterpret_cast<int32_t*>(p.part_s + (int64_t)plan.vocab_splits * plan.rows_per_chunk);
+  p.out_token = a.out_token;
+  p.out_conf = a.out_conf;
+  p.out_lse = a.out_lse;
+
+  for (int c = 0; c < plan.num_chunks; ++c) {
+    const int64_t row0 = (int64_t)c * plan.rows_per_chunk;
+    if (row0 >= a.max_rows) break;
+    p.row0 = (int32_t)row0;
+    int64_t cap = a.max_rows - row0;
+    if (cap > plan.rows_per_chunk) cap = plan.rows_per_chunk;
+    const int64_t tiles = (cap + kTileRows - 1) / kTileRows;
+    int64_t grid = tiles * plan.vocab_splits;
+    if (grid > plan.grid) grid = plan.grid;
+    switch (variant) {
+      case 1:
+        hipLaunchKernelGGL((masked_logits_kernel<2, 0>), dim3((unsigned)grid), dim3(kThreads), 0, stream, p);
+        break;
+      case 2:
+        hipLaunchKernelGGL((masked_logits_kernel<2, 2>), dim3((unsigned)grid), dim3(kThreads), 0, stream, p);
+        break;
+      default:
+        hipLaunchKernelGGL((masked_logits_kernel<2, 1>), dim3((unsigned)grid), dim3(kThreads), 0, stream, p);
+        break;
+    }
+    hipLaunchKernelGGL(combine_kernel, dim3((unsigned)((cap + 255) / 256)), dim3(256), 0, stream, p);
+  }
+  return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+}  // namespace mosaic

@@ -1,0 +1,73 @@
+// Host-side chunk-size selector for the mask-only logits path.
+//
+// Paper section 4.4: chunking of the logits operator along the sequence dimension is off by
+// default ("lazy") and switched on only when memory is short; the search raises the chunk count of
+// the operator that forms the peak by one, re-evaluates the footprint, and stops at the first
+// configuration that fits, or fails when only non-chunkable memory is left.  On this path the one
+// chunkable buffer is the array of partial (max, sum-exp, arg-max) triples, 12 bytes per row and
+// vocabulary split; its non-chunkable floor is one row tile with one split.
+#include <stdint.h>
+
+#include "mosaic_internal.h"
+
+namespace mosaic {
+
+int64_t partials_bytes(int64_t rows_padded, int32_t splits) { return 12 * rows_padded * (int64_t)splits; }
+
+// Number of vocabulary splits for `row_tiles` row tiles: the workgroups walk their units in rounds of
+// `num_cus`; a round lasts as long as its longest unit.  Pick the S that minimises
+// rounds * (tiles per unit + a fixed per-unit cost), the smallest S on ties.
+int32_t choose_vocab_splits(int64_t row_tiles, int64_t vocab_tiles, int32_t num_cus) {
+  if (row_tiles <= 0 || vocab_tiles <= 0) return 1;
+  int64_t smax = vocab_tiles < MOSAIC_MAX_VOCAB_SPLITS ? vocab_tiles : MOSAIC_MAX_VOCAB_SPLITS;
+  int32_t best = 1;
+  int64_t best_cost = -1;
+  for (int64_t s = 1; s <= smax; ++s) {
+    const int64_t units = row_tiles * s;
+    const int64_t rounds = (units + num_cus - 1) / num_cus;
+    const int64_t longest = (vocab_tiles + s - 1) / s;
+    const int64_t cost = rounds * (4 * longest + 1);  // quarter-tile units: 1/4 tile of overhead per unit
+    if (best_cost < 0 || cost < best_cost) {
+      best_cost = cost;
+      best = (int32_t)s;
+    }
+  }
+  return best;
+}
+
+}  // namespace mosaic
+
+extern "C" int mosaic_plan_workspace(int64_t T, int64_t max_rows, int32_t d, int32_t V, int64_t budget_bytes,
+                                     int32_t num_cus, mosaic_plan* out_plan) {
+  using namespace mosaic;
+  if (out_plan == nullptr || T < 0 || max_rows < 0 || max_rows > T || d <= 0 || V < 0) return MOSAIC_ERR_INVALID_ARG;
+  if (T >= (int64_t)1 << 31 || (int64_t)V >= ((int64_t)1 << 31) - MOSAIC_VOCAB_TILE || d % MOSAIC_K_TILE != 0)
+    return MOSAIC_ERR_UNSUPPORTED_SHAPE;
+  if (num_cus <= 0) num_cus = 256;
+  const int64_t vocab_tiles = ((int64_t)V + MOSAIC_VOCAB_TILE - 1) / MOSAIC_VOCAB_TILE;
+  const int64_t rows = max_rows > 0 ? max_rows : 1;
+
+  for (int64_t K = 1;; ++K) {
+    const int64_t per = (rows + K - 1) / K;
+    const int64_t C = (per + MOSAIC_ROW_TILE - 1) / MOSAIC_ROW_TILE * MOSAIC_ROW_TILE;
+    const int64_t row_tiles = C / MOSAIC_ROW_TILE;
+    int64_t S = choose_vocab_splits(row_tiles, vocab_tiles, num_cus);
+    if (budget_bytes > 0) {
+      const int64_t fit = budget_bytes / partials_bytes(C, 1);  // splits the budget allows
+      if (fit < S) S = fit;
+    }
+    if (S >= 1) {
+      out_plan->workspace_bytes = partials_bytes(C, (int32_t)S);
+      out_plan->num_chunks = (int32_t)((rows + C - 1) / C);  // chunks that actually hold rows
+      out_plan->rows_per_chunk = (int32_t)C;
+      out_plan->vocab_splits = (int32_t)S;
+      out_plan->tile_panel = (int32_t)(row_tiles <= 16 ? row_tiles : 8);
+      int64_t grid = row_tiles * S;
+      if (grid > num_cus) grid = num_cus;
+      out_plan->grid = (int32_t)grid;
+      out_plan->reserved = 0;
+      return MOSAIC_OK;
+    }
+    if (C == MOSAIC_ROW_TILE) return MOSAIC_ERR_WORKSPACE_TOO_SMALL;  // nothing left to chunk
+  }
+}

@@ -1,0 +1,71 @@
+"""Full-size parity on the five benchmark workloads, in the launch configuration bench.py times:
+sampled rows against the oracle (rows are independent, so a sample is the restriction of the full
+oracle), plus properties that hold on every row."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2601_06562_amd import workloads
+
+from gpu_helpers import check_against_oracle, oracle_rows, run_hip
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+SAMPLE = 96
+
+
+def sample_rows(M, rng, tile=256, extra=()):
+    """Stratified sample of compacted row numbers: ends, tile boundaries, then random."""
+    picks = {0, M - 1, *[e for e in extra if 0 <= e < M]}
+    for b in range(tile, M, tile):
+        if len(picks) < SAMPLE // 2:
+            picks.update({b - 1, b})
+    while len(picks) < min(SAMPLE, M):
+        picks.add(int(rng.integers(0, M)))
+    return np.array(sorted(picks), dtype=np.int64)
+
+
+@pytest.mark.parametrize("name", ["llada_first_step", "long_semi_ar", "dream_late_step", "batched_mixed"])
+def test_full_size_workload(name):
+    print(f"full-size {name}: generating", flush=True)
+    wl = workloads.make(name, device=DEV)
+    M_true = wl.M
+    print(f"full-size {name}: T={wl.T} d={wl.d} V={wl.V} M={M_true}; HIP path", flush=True)
+    out = run_hip(wl.hidden, wl.w, wl.mask, max_rows=M_true)
+    M = out["M"]
+    assert M == M_true
+    # compaction: bit-exact against the definition (ascending positions with a nonzero byte)
+    want_idx = torch.nonzero(wl.mask.cpu(), as_tuple=False).flatten().numpy().astype(np.int32)
+    assert np.array_equal(out["idx"][:M], want_idx)
+    tok, conf, lse = out["tok"][:M], out["conf"][:M], out["lse"][:M]
+    # whole-output properties
+    assert np.all(np.isfinite(lse)) and np.all((conf > 0) & (conf <= 1.0 + 1e-6))
+    assert np.all((tok >= 0) & (tok < wl.V))
+    implied_max = lse + np.log(conf)
+    assert np.all(implied_max > 1.0) and np.all(implied_max < 16.0)      # ~ sigma * sqrt(2 ln V), sigma in [0.5, 2]
+    assert abs(float(np.mean(lse)) - (math.log(wl.V) + (0.5 if name != "batched_mixed" else 0.875))) < 0.2
+    plan = out["op"].plan
+    assert out["op"].workspace_bytes < 4 * M * wl.V / 50                 # nowhere near an [M,V] fp32 tensor
+    print(f"full-size {name}: plan {plan}; oracle on {SAMPLE} rows", flush=True)
+    rng = np.random.default_rng(11)
+    extra = []
+    if name == "batched_mixed":                                          # rows of every sequence, incl. the 2% one
+        bounds = np.searchsorted(want_idx, np.arange(0, wl.T + 1, 16384))
+        for b in range(8):
+            extra += [int(bounds[b]), int(bounds[b + 1]) - 1, int((bounds[b] + bounds[b + 1]) // 2)]
+    rows = sample_rows(M, rng, extra=extra)
+    w_bits = workloads.bf16_bits(wl.w)
+    want, logits = oracle_rows(wl.hidden, w_bits, want_idx[rows], return_logits=True)
+    stats = check_against_oracle(dict(tok=tok[rows], conf=conf[rows], lse=lse[rows]), want, logits, what=name)
+    print(f"full-size {name}: {stats}", flush=True)
+    # "select": an unmasked position's row, computed by forcing it into a second mask, matches the oracle too
+    if M < wl.T:
+        unmasked = torch.nonzero(wl.mask == 0).flatten()[:8]
+        m2 = torch.zeros_like(wl.mask)
+        m2[unmasked] = 1
+        out2 = run_hip(wl.hidden, wl.w, m2, max_rows=8)
+        want2 = oracle_rows(wl.hidden, w_bits, unmasked.cpu().numpy())
+        check_against_oracle(dict(tok=out2["tok"][:8], conf=out2["conf"][:8], lse=out2["lse"][:8]), want2,
+                             what=name + " unmasked rows")

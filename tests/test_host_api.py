@@ -1,0 +1,120 @@
+"""Host-side logic of libmosaic that needs no GPU: the library loads and exports every symbol the
+header declares, the chunk-size selector against brute force, and argument validation (errors are
+raised before anything is enqueued, so null device pointers are never dereferenced)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2601_06562_amd import binding
+from paper_2601_06562_amd.binding import MosaicPlan
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "mosaic.h")).read()
+    declared = set(re.findall(r"\b(mosaic_[a-z_]+)\s*\(", header))
+    assert declared == set(binding.EXPORTS)
+    L = binding.lib()
+    for name in declared:
+        assert getattr(L, name) is not None
+    assert L.mosaic_version() >= 1000
+    assert binding.status_string(0) == "MOSAIC_OK"
+    assert binding.status_string(-3) == "MOSAIC_ERR_WORKSPACE_TOO_SMALL"
+
+
+def workspace(C, S):
+    return 12 * C * S
+
+
+def brute_force_min_chunks(max_rows, budget):
+    """Smallest K whose chunk fits with a single split, by enumeration (section 4.4: minimal K)."""
+    rows = max(max_rows, 1)
+    for K in range(1, rows + 1):
+        C = -(-(-(-rows // K)) // 256) * 256
+        if workspace(C, 1) <= budget:
+            return K, C
+    return None
+
+
+@pytest.mark.parametrize("rows", [1, 255, 256, 257, 4096, 6554, 58491, 131072])
+def test_selector_unbounded_is_one_chunk(rows):
+    plan = binding.mosaic_plan_workspace(131072, rows, 4096, 126464, 0)
+    assert plan.num_chunks == 1 and plan.rows_per_chunk >= rows and plan.rows_per_chunk % 256 == 0
+    assert plan.workspace_bytes == workspace(plan.rows_per_chunk, plan.vocab_splits)
+    assert 1 <= plan.vocab_splits <= 64 and 1 <= plan.grid <= 256
+
+
+@pytest.mark.parametrize("rows", [300, 4096, 5000, 58491])
+@pytest.mark.parametrize("budget", [3072, 3073, 12 * 256 * 7, 12 * 1024, 12 * 4096, 100000, 10 ** 6])
+def test_selector_matches_brute_force(rows, budget):
+    plan = binding.mosaic_plan_workspace(131072, rows, 4096, 126464, budget)
+    K, C = brute_force_min_chunks(rows, budget)
+    assert plan.rows_per_chunk == C                      # minimal K <=> largest chunk that fits
+    assert plan.num_chunks == -(-rows // C)
+    assert plan.workspace_bytes <= budget
+    assert plan.num_chunks * plan.rows_per_chunk >= rows
+    # lazy: a roomier budget never needs more chunks
+    roomy = binding.mosaic_plan_workspace(131072, rows, 4096, 126464, budget * 2)
+    assert roomy.num_chunks <= plan.num_chunks
+
+
+def test_selector_failure_is_exactly_the_non_chunkable_floor():
+    with pytest.raises(binding.MosaicError) as e:
+        binding.mosaic_plan_workspace(4096, 4096, 4096, 126464, 3071)
+    assert e.value.status == binding.MOSAIC_ERR_WORKSPACE_TOO_SMALL
+    assert binding.mosaic_plan_workspace(4096, 4096, 4096, 126464, 3072).rows_per_chunk == 256
+
+
+def test_selector_split_choice_fills_the_chip():
+    plan = binding.mosaic_plan_workspace(4096, 4096, 4096, 126464, 0)
+    assert plan.vocab_splits == 16 and plan.grid == 256          # 16 row tiles x 16 splits = 256 CUs
+    plan = binding.mosaic_plan_workspace(131072, 58491, 4096, 126464, 0)
+    units = (plan.rows_per_chunk // 256) * plan.vocab_splits
+    rounds = -(-units // 256)
+    assert units / (rounds * 256) > 0.97
+
+
+def test_selector_rejects_bad_arguments():
+    L = binding.lib()
+    plan = MosaicPlan()
+    ok = lambda *a: L.mosaic_plan_workspace(*a, ctypes.byref(plan))
+    assert ok(-1, 0, 4096, 1000, 0, 0) == binding.MOSAIC_ERR_INVALID_ARG
+    assert ok(10, 11, 4096, 1000, 0, 0) == binding.MOSAIC_ERR_INVALID_ARG
+    assert ok(10, 10, 4000, 1000, 0, 0) == binding.MOSAIC_ERR_UNSUPPORTED_SHAPE
+    assert ok(2 ** 31, 10, 4096, 1000, 0, 0) == binding.MOSAIC_ERR_UNSUPPORTED_SHAPE
+    assert L.mosaic_plan_workspace(10, 10, 4096, 1000, 0, 0, None) == binding.MOSAIC_ERR_INVALID_ARG
+    assert ok(0, 0, 64, 1, 0, 0) == binding.MOSAIC_OK
+
+
+def test_entry_points_validate_before_launch():
+    L = binding.lib()
+    null = ctypes.c_void_p(0)
+    fake = ctypes.c_void_p(0x1000)        # never dereferenced: validation fails first
+    assert L.mosaic_mask_compact(null, 16, fake, fake, fake, 1 << 20, null) == binding.MOSAIC_ERR_INVALID_ARG
+    assert L.mosaic_mask_compact(fake, -1, fake, fake, fake, 1 << 20, null) == binding.MOSAIC_ERR_INVALID_ARG
+    assert L.mosaic_mask_compact(fake, 2 ** 31, fake, fake, fake, 1 << 30, null) == binding.MOSAIC_ERR_UNSUPPORTED_SHAPE
+    assert L.mosaic_mask_compact(fake, 10 ** 6, fake, fake, fake, 8, null) == binding.MOSAIC_ERR_INVALID_ARG
+    assert binding.mosaic_compact_scratch_bytes(0) >= 4 and binding.mosaic_compact_scratch_bytes(10 ** 6) >= 4 * 245
+    plan = binding.mosaic_plan_workspace(4096, 4096, 4096, 126464, 0)
+    P = ctypes.byref(plan)
+    call = lambda **kw: L.mosaic_masked_logits_reduce(
+        kw.get("hidden", fake), kw.get("T", 4096), kw.get("d", 4096), kw.get("ld_h", 4096), kw.get("w", fake),
+        kw.get("V", 126464), fake, kw.get("count", fake), kw.get("max_rows", 4096), fake, fake, fake,
+        kw.get("plan", P), kw.get("ws", fake), kw.get("ws_bytes", plan.workspace_bytes), null)
+    assert call(hidden=null) == binding.MOSAIC_ERR_INVALID_ARG
+    assert call(count=null) == binding.MOSAIC_ERR_INVALID_ARG
+    assert call(hidden=ctypes.c_void_p(0x1008)) == binding.MOSAIC_ERR_INVALID_ARG          # misaligned
+    assert call(d=4090) == binding.MOSAIC_ERR_UNSUPPORTED_SHAPE
+    assert call(ld_h=4000) == binding.MOSAIC_ERR_UNSUPPORTED_SHAPE
+    assert call(ld_h=4100) == binding.MOSAIC_ERR_UNSUPPORTED_SHAPE
+    assert call(ws_bytes=plan.workspace_bytes - 1) == binding.MOSAIC_ERR_WORKSPACE_TOO_SMALL
+    assert call(max_rows=5000) == binding.MOSAIC_ERR_INVALID_ARG                            # > T
+    assert call(max_rows=0) == binding.MOSAIC_OK                                            # nothing to do
+    bad = MosaicPlan.from_buffer_copy(plan)
+    bad.vocab_splits = 0
+    assert call(plan=ctypes.byref(bad)) == binding.MOSAIC_ERR_INVALID_ARG
+    small = binding.mosaic_plan_workspace(4096, 256, 4096, 126464, 0)                       # plan for fewer rows
+    assert call(plan=ctypes.byref(small), ws_bytes=1 << 30) == binding.MOSAIC_ERR_INVALID_ARG
