@@ -1,0 +1,125 @@
+"""Benchmark of the mask-only logits hot path on one MI355X.
+
+A step = one pass of the whole path over one batch of synthetic input already resident in HBM:
+mosaic_mask_compact (mask -> indices) followed by mosaic_masked_logits_reduce (gather-GEMM against
+the LM head fused with the vocabulary reduction, then the split merge).  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload llada_first_step] [--no-cpu-baseline]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak (2.5 PFLOP/s)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="llada_first_step")
+    ap.add_argument("--budget-bytes", type=int, default=0, help="workspace budget for the chunk-size selector")
+    ap.add_argument("--cpu-rows", type=int, default=4096, help="rows of the workload the CPU oracle is timed on")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.exit("bench.py: this path is built and measured on ONE GPU; --gpus N with N > 1 is not supported "
+                 "(rows are independent, so N GPUs would each run this same kernel on M/N rows)")
+
+    import numpy as np
+    import torch
+    from paper_2601_06562_amd import MaskOnlyLogits, binding, workloads
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    binding.lib()   # fail loudly if the HIP library is not built
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    wl = workloads.make(args.workload, device=dev)
+    M = wl.M
+    op = MaskOnlyLogits(wl.T, wl.d, wl.V, max_rows=M, budget_bytes=args.budget_bytes, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def step(ev=None):
+        binding.mosaic_mask_compact(wl.mask, op.idx, op.count, op.scratch, stream)
+        if ev is not None:
+            ev[0].record(stream)
+        binding.mosaic_masked_logits_reduce(wl.hidden, wl.w, op.idx, op.count, op.max_rows, op.token, op.conf,
+                                            op.lse, op.plan, op.workspace, stream)
+        if ev is not None:
+            ev[1].record(stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(events[k])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    assert int(op.count.item()) == M
+    sec_per_step = (t1 - t0) / args.steps
+    kern_ms = float(np.mean([a.elapsed_time(b) for a, b in events]))   # fused kernel (+ the tiny merge)
+
+    flop = 2.0 * M * wl.d * wl.V
+    tflops = flop / (kern_ms * 1e-3) / 1e12
+    out = {
+        "metric": "masked tokens/sec for mask-only logits (compact + fused gather-GEMM/vocab reduction)",
+        "value": M / sec_per_step,
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": sec_per_step * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": args.workload, "T": wl.T, "d": wl.d, "V": wl.V, "masked_rows": M,
+                   "num_chunks": op.plan.num_chunks, "rows_per_chunk": op.plan.rows_per_chunk,
+                   "vocab_splits": op.plan.vocab_splits, "grid": op.plan.grid},
+        "tflops": flop / sec_per_step / 1e12,
+        "pct_bf16_mfma_peak": 100.0 * flop / sec_per_step / 1e12 / PEAK_BF16_TFLOPS,
+        "peak_workspace_bytes": op.workspace_bytes,
+        "logits_bytes_avoided": {"fp32_MxV": 4 * M * wl.V, "fp32_TxV": 4 * wl.T * wl.V},
+        "roofline": {"bound": "mfma", "kernel": "masked_logits_kernel", "achieved": tflops,
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": tflops / PEAK_BF16_TFLOPS,
+                     "kernel_ms": kern_ms, "flop_per_launch": flop, "traffic": None},
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        rows = min(args.cpu_rows, M)
+        rng = np.random.default_rng(0)
+        pick = np.sort(rng.choice(M, size=rows, replace=False))
+        pos = op.idx[:M][torch.as_tensor(pick, device=dev)].long()
+        h_bits = workloads.bf16_bits(wl.hidden[pos])
+        w_bits = workloads.bf16_bits(wl.w)
+        oracle.positions(h_bits[:2], w_bits, np.arange(2))          # page in, build
+        c0 = time.perf_counter()
+        want = oracle.positions(h_bits, w_bits, np.arange(rows))
+        c1 = time.perf_counter()
+        got_tok = op.token[:M].cpu().numpy()[pick]
+        got_lse = op.lse[:M].cpu().numpy()[pick]
+        strict = want.gap > 1e-2
+        out["cpu_baseline"] = {
+            "value": rows / (c1 - c0), "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"{rows} of the {M} masked rows of {args.workload}, all {wl.V} logits each "
+                      f"(fp64-accumulated), {c1 - c0:.1f} s",
+            "parity_on_sample": {"max_abs_dlse": float(np.abs(got_lse - want.lse).max()),
+                                 "argmax_equal_on_strict_rows": bool(np.array_equal(got_tok[strict], want.tok[strict])),
+                                 "strict_rows": int(strict.sum())},
+        }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

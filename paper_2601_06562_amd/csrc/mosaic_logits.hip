@@ -102,6 +102,15 @@ __device__ __forceinline__ void wait_stage(int tiles_after) {
   }
 }
 
+// exp(x - mn) as exp2.  Full tiles fold the subtraction into one fma against nml = -mn*log2(e).  Tail
+// tiles hold the kNeg sentinel, whose magnitude would turn the rounding of nml into a huge exponent, so
+// they subtract first (exact zero when x == mn).
+template <bool TAIL>
+__device__ __forceinline__ float exp_rel(float x, float mn, float nml) {
+  if constexpr (TAIL) return __builtin_amdgcn_exp2f((x - mn) * kLog2e);
+  else return __builtin_amdgcn_exp2f(__builtin_fmaf(x, kLog2e, nml));
+}
+
 // Reduce one finished 256x256 logits tile (this wave's 128 vocabulary ids x 64 tokens) into the
 // lane's running triples.  vb = vocabulary id of this lane's element (block 0, register 0).
 template <bool TAIL>
@@ -139,10 +148,10 @@ __device__ __forceinline__ void reduce_tile(f32x16 (&acc)[4][2], float (&m)[2], 
     for (int bi = 0; bi < 4; ++bi) {
 #pragma unroll
       for (int r = 0; r < 16; r += 4) {
-        p0 += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[bi][bj][r + 0], kLog2e, nml));
-        p1 += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[bi][bj][r + 1], kLog2e, nml));
-        p2 += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[bi][bj][r + 2], kLog2e, nml));
-        p3 += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[bi][bj][r + 3], kLog2e, nml));
+        p0 += exp_rel<TAIL>(acc[bi][bj][r + 0], mn, nml);
+        p1 += exp_rel<TAIL>(acc[bi][bj][r + 1], mn, nml);
+        p2 += exp_rel<TAIL>(acc[bi][bj][r + 2], mn, nml);
+        p3 += exp_rel<TAIL>(acc[bi][bj][r + 3], mn, nml);
       }
     }
     s[bj] = s[bj] * __builtin_amdgcn_exp2f((m[bj] - mn) * kLog2e) + ((p0 + p1) + (p2 + p3));
