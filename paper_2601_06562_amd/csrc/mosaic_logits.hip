@@ -20,9 +20,11 @@
 // row in fixed order (deterministic) and emits token, confidence and log-sum-exp.
 //
 // Data movement.  Global->LDS copies use the direct-to-LDS 16-byte loads of gfx950; both tiles are
-// K-contiguous ([256 rows][64 k] bf16 = 128 B per row) and 16-byte chunks are XOR-swizzled by row so
-// that the ds_read_b128 operand fetches of 32 consecutive rows spread over all LDS banks.  A ring of
-// stages is filled one K-tile ahead; one workgroup barrier per K-tile.
+// K-contiguous ([256 rows][64 k] bf16 = 128 B per row, i.e. whole 128-byte lines per request) and
+// 16-byte chunks are XOR-swizzled by row so that the ds_read_b128 operand fetches of 32 consecutive
+// rows spread over all LDS banks.  Each operand has its own ring of 32 KiB slots: three for the LM-head
+// tiles (two K-tiles ahead), two for the hidden tiles (one ahead) -- 160 KiB, all of a CU's LDS; the
+// merge scratch aliases slot 0 at the end of a unit.  One workgroup barrier per K-tile.
 #include <hip/hip_runtime.h>
 #include <limits.h>
 #include <stdint.h>
@@ -39,12 +41,7 @@ typedef const __attribute__((address_space(1))) void* gbl_ptr_t;
 
 constexpr int kTileRows = MOSAIC_ROW_TILE;     // masked tokens per tile (MFMA N side)
 constexpr int kTileVocab = MOSAIC_VOCAB_TILE;  // vocabulary ids per tile (MFMA M side)
-constexpr int kTileK = MOSAIC_K_TILE;          // 64 bf16 = 128 bytes per row per stage
 constexpr int kThreads = 512;                  // 8 waves: 2 (vocabulary halves) x 4 (token quarters)
-constexpr int kRowBytes = kTileK * 2;
-constexpr int kOperandBytes = 256 * kRowBytes;       // 32 KiB per operand tile
-constexpr int kStageBytes = 2 * kOperandBytes;       // W tile then H tile
-constexpr int kLoadsPerStage = 8;                    // direct-to-LDS instructions per wave per stage
 constexpr float kNeg = -1.0e30f;                     // "minus infinity" that survives subtraction
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
@@ -86,20 +83,6 @@ __device__ __forceinline__ void merge_triple(float& m, float& s, int& i, float m
 template <int N>
 __device__ __forceinline__ void wait_vm() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
-
-// Wait until at most `tiles_after` later stages (8 loads each) are still in flight.
-template <int NST>
-__device__ __forceinline__ void wait_stage(int tiles_after) {
-  if constexpr (NST <= 2) {
-    wait_vm<0>();
-  } else if constexpr (NST == 3) {
-    if (tiles_after >= 1) wait_vm<kLoadsPerStage>(); else wait_vm<0>();
-  } else {
-    if (tiles_after >= 2) wait_vm<2 * kLoadsPerStage>();
-    else if (tiles_after == 1) wait_vm<kLoadsPerStage>();
-    else wait_vm<0>();
-  }
 }
 
 // exp(x - mn) as exp2.  Full tiles fold the subtraction into one fma against nml = -mn*log2(e).  Tail
@@ -159,11 +142,23 @@ __device__ __forceinline__ void reduce_tile(f32x16 (&acc)[4][2], float (&m)[2], 
   }
 }
 
-template <int NST, int SWZ>
+// Separate rings for the two operands: NW slots of W K-tiles, NH slots of H K-tiles (32 KiB each).
+// The shallow ring runs one K-tile ahead, the deep one two; the shallow operand is issued first in
+// every iteration so that the in-order vmcnt wait can leave the deep ring's newest tile in flight.
+template <int NW, int NH>
 __global__ __launch_bounds__(kThreads) void masked_logits_kernel(const KernelParams p) {
-  constexpr int kRing = NST * kStageBytes;
-  __shared__ __attribute__((aligned(1024))) char smem[kRing + 3 * 256 * 4];
-  float* red_m = reinterpret_cast<float*>(smem + kRing);
+  static_assert((NW == 2 || NW == 3) && (NH == 2 || NH == 3) && NW + NH <= 5, "ring shape");
+  constexpr int kTileK = 64;
+  constexpr int kRowBytes = 128;
+  constexpr int kOperandBytes = 256 * kRowBytes;        // 32 KiB
+  constexpr int kSwzShift = 1;
+  constexpr int kSubSteps = 4;
+  constexpr int kDW = NW - 1, kDH = NH - 1;             // prefetch distance in K-tiles
+  constexpr int kRing = (NW + NH) * kOperandBytes;
+  constexpr int kLds = (NW + NH == 5) ? kRing : kRing + 3 * 256 * 4;
+  constexpr int kRedOff = (NW + NH == 5) ? 0 : kRing;   // 5 slots fill the LDS: merge scratch aliases slot 0
+  __shared__ __attribute__((aligned(1024))) char smem[kLds];
+  float* red_m = reinterpret_cast<float*>(smem + kRedOff);
   float* red_s = red_m + 256;
   int* red_i = reinterpret_cast<int*>(red_s + 256);
 
@@ -179,8 +174,6 @@ __global__ __launch_bounds__(kThreads) void masked_logits_kernel(const KernelPar
   if (rows <= 0) return;
   const int n_tt = (rows + kTileRows - 1) / kTileRows;
 
-  // Position in the schedule.  Workgroups are dealt round-robin to the 8 XCDs, so workgroups
-  // b, b+8, b+16, ... share an L2: give them consecutive units.
   const int G = gridDim.x;
   int pos = blockIdx.x;
   if ((G & 7) == 0) pos = (int)(blockIdx.x & 7) * (G >> 3) + (int)(blockIdx.x >> 3);
@@ -190,17 +183,13 @@ __global__ __launch_bounds__(kThreads) void masked_logits_kernel(const KernelPar
   const int full_panel_units = A * S;
   const int n_panels = (n_tt + A - 1) / A;
 
-  // Direct-to-LDS copy: instruction i of this wave fills rows wave*32 + 8*i + lane/8 of a tile,
-  // lane%8 is the physical 16-byte chunk; the logical chunk fetched there is swizzled by the row.
   const int drow = wave * 32 + (lane >> 3);
   int src_chunk_bytes[4];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) src_chunk_bytes[i] = (((lane & 7) ^ (((drow + 8 * i) >> SWZ) & 7))) * 16;
-
-  // MFMA operand fetch: row = 32-row block base + lane%32, logical chunk 2*ks + lane/32.
-  int rd_off[4];
+  for (int i = 0; i < 4; ++i) src_chunk_bytes[i] = (((lane & 7) ^ (((drow + 8 * i) >> kSwzShift) & 7))) * 16;
+  int rd_off[kSubSteps];
 #pragma unroll
-  for (int ks = 0; ks < 4; ++ks) rd_off[ks] = l32 * kRowBytes + (((2 * ks + lhalf) ^ ((l32 >> SWZ) & 7)) * 16);
+  for (int ks = 0; ks < kSubSteps; ++ks) rd_off[ks] = l32 * kRowBytes + (((2 * ks + lhalf) ^ ((l32 >> kSwzShift) & 7)) * 16);
 
   const int nk = p.d / kTileK;
 
@@ -216,8 +205,6 @@ __global__ __launch_bounds__(kThreads) void masked_logits_kernel(const KernelPar
     const int ntile = vt1 - vt0;
     const int total_steps = ntile * nk;
 
-    // Gather: per-lane base pointers of the 4 hidden rows this lane copies.  Rows past the end of
-    // the chunk re-read the last valid row; their results are never stored.
     const char* hptr[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -228,33 +215,51 @@ __global__ __launch_bounds__(kThreads) void masked_logits_kernel(const KernelPar
     }
     const char* wptr[4];
 
-    int ld_vt = vt0, ld_k = 0, ld_stage = 0, ld_issued = 0;
-    auto issue = [&]() {
-      if (ld_k == 0) {
+    // W loader: global step w_g = (vocab tile, k); slot w_g % NW.
+    int w_g = 0, w_vt = vt0, w_k = 0, w_slot = 0;
+    auto issue_w = [&]() {
+      if (w_k == 0) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          int v = ld_vt * kTileVocab + drow + 8 * i;
-          if (v > p.V - 1) v = p.V - 1;  // tail tile: clamp, masked in the reduction
+          int v = w_vt * kTileVocab + drow + 8 * i;
+          if (v > p.V - 1) v = p.V - 1;
           wptr[i] = p.w + (int64_t)v * ((int64_t)p.d * 2) + src_chunk_bytes[i];
         }
       }
-      char* stage = smem + ld_stage * kStageBytes + (wave * 32) * kRowBytes;
-      const int koff = ld_k * kRowBytes;
+      char* dst = smem + w_slot * kOperandBytes + (wave * 32) * kRowBytes;
+      const int koff = w_k * kRowBytes;
 #pragma unroll
       for (int i = 0; i < 4; ++i)
-        __builtin_amdgcn_global_load_lds((gbl_ptr_t)(wptr[i] + koff), (lds_ptr_t)(stage + i * 8 * kRowBytes), 16, 0, 0);
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        __builtin_amdgcn_global_load_lds((gbl_ptr_t)(hptr[i] + koff),
-                                         (lds_ptr_t)(stage + kOperandBytes + i * 8 * kRowBytes), 16, 0, 0);
-      ld_k += 1;
-      if (ld_k == nk) {
-        ld_k = 0;
-        ld_vt += 1;
-      }
-      ld_stage = (ld_stage + 1 == NST) ? 0 : ld_stage + 1;
-      ld_issued += 1;
+        __builtin_amdgcn_global_load_lds((gbl_ptr_t)(wptr[i] + koff), (lds_ptr_t)(dst + i * 1024), 16, 0, 0);
+      w_k += 1;
+      if (w_k == nk) { w_k = 0; w_vt += 1; }
+      w_slot = (w_slot + 1 == NW) ? 0 : w_slot + 1;
+      w_g += 1;
     };
+    int h_g = 0, h_k = 0, h_slot = 0;
+    auto issue_h = [&]() {
+      char* dst = smem + (NW + h_slot) * kOperandBytes + (wave * 32) * kRowBytes;
+      const int koff = h_k * kRowBytes;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        __builtin_amdgcn_global_load_lds((gbl_ptr_t)(hptr[i] + koff), (lds_ptr_t)(dst + i * 1024), 16, 0, 0);
+      h_k = (h_k + 1 == nk) ? 0 : h_k + 1;
+      h_slot = (h_slot + 1 == NH) ? 0 : h_slot + 1;
+      h_g += 1;
+    };
+    // One scheduling slot: at (virtual) iteration it, bring in W step it+kDW and H step it+kDH,
+    // shallow ring first.
+    auto issue_pair = [&](int it) {
+      if constexpr (kDW <= kDH) {
+        if (it + kDW >= 0 && it + kDW < total_steps) issue_w();
+        if (it + kDH >= 0 && it + kDH < total_steps) issue_h();
+      } else {
+        if (it + kDH >= 0 && it + kDH < total_steps) issue_h();
+        if (it + kDW >= 0 && it + kDW < total_steps) issue_w();
+      }
+    };
+    constexpr int kDMax = kDW > kDH ? kDW : kDH;
+    constexpr int kDMin = kDW < kDH ? kDW : kDH;
 
     float run_m[2] = {kNeg, kNeg};
     float run_s[2] = {0.f, 0.f};
@@ -262,10 +267,9 @@ __global__ __launch_bounds__(kThreads) void masked_logits_kernel(const KernelPar
 
     wait_vm<0>();
 #pragma unroll
-    for (int q = 0; q < NST - 1; ++q)
-      if (ld_issued < total_steps) issue();
+    for (int it = -kDMax; it < 0; ++it) issue_pair(it);
 
-    int st = 0, step = 0;
+    int ws = 0, hs = 0, step = 0;
     for (int n = 0; n < ntile; ++n) {
       f32x16 acc[4][2];
 #pragma unroll
@@ -276,14 +280,17 @@ __global__ __launch_bounds__(kThreads) void masked_logits_kernel(const KernelPar
           for (int r = 0; r < 16; ++r) acc[bi][bj][r] = 0.f;
 
       for (int kt = 0; kt < nk; ++kt, ++step) {
-        wait_stage<NST>(ld_issued - step - 1);
-        __builtin_amdgcn_s_barrier();  // stage `st` is complete for every wave; stage st-1 is free
-        if (ld_issued < total_steps) issue();
+        // Both operands of `step` must have landed.  The only loads issued after them are the deep
+        // ring's tile step+kDMax... (one tile, 4 loads) when the rings differ in depth by one.
+        if (kDMax > kDMin && step + kDMax - kDMin < total_steps && kDMin == 1) wait_vm<4>();
+        else wait_vm<0>();
+        __builtin_amdgcn_s_barrier();
+        issue_pair(step);
 
-        const char* wbase = smem + st * kStageBytes + (wv * 128) * kRowBytes;
-        const char* hbase = smem + st * kStageBytes + kOperandBytes + (wt * 64) * kRowBytes;
+        const char* wbase = smem + ws * kOperandBytes + (wv * 128) * kRowBytes;
+        const char* hbase = smem + (NW + hs) * kOperandBytes + (wt * 64) * kRowBytes;
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
+        for (int ks = 0; ks < kSubSteps; ++ks) {
           bf16x8 a[4], b[2];
 #pragma unroll
           for (int bi = 0; bi < 4; ++bi) a[bi] = *reinterpret_cast<const bf16x8*>(wbase + bi * 32 * kRowBytes + rd_off[ks]);
@@ -295,7 +302,8 @@ __global__ __launch_bounds__(kThreads) void masked_logits_kernel(const KernelPar
             for (int bj = 0; bj < 2; ++bj)
               acc[bi][bj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[bi], b[bj], acc[bi][bj], 0, 0, 0);
         }
-        st = (st + 1 == NST) ? 0 : st + 1;
+        ws = (ws + 1 == NW) ? 0 : ws + 1;
+        hs = (hs + 1 == NH) ? 0 : hs + 1;
       }
 
       const int v_tile0 = (vt0 + n) * kTileVocab;
@@ -304,8 +312,6 @@ __global__ __launch_bounds__(kThreads) void masked_logits_kernel(const KernelPar
       else reduce_tile<false>(acc, run_m, run_s, run_i, vb, p.V);
     }
 
-    // Unit end: fold the two lanes that share a token (lane ^ 32), then the two waves that share
-    // it (vocabulary halves) through LDS, and publish one partial triple per row.
 #pragma unroll
     for (int bj = 0; bj < 2; ++bj) {
       const float m2 = __shfl_xor(run_m[bj], 32, 64);
@@ -313,6 +319,7 @@ __global__ __launch_bounds__(kThreads) void masked_logits_kernel(const KernelPar
       const int i2 = __shfl_xor(run_i[bj], 32, 64);
       merge_triple(run_m[bj], run_s[bj], run_i[bj], m2, s2, i2);
     }
+    __syncthreads();  // every wave is done reading the ring (the merge scratch may alias it)
     if (wv == 1 && lhalf == 0) {
 #pragma unroll
       for (int bj = 0; bj < 2; ++bj) {
@@ -322,7 +329,7 @@ __global__ __launch_bounds__(kThreads) void masked_logits_kernel(const KernelPar
         red_i[e] = run_i[bj];
       }
     }
-    __syncthreads();  // also: every wave is done with the ring before the next unit refills it
+    __syncthreads();
     if (wv == 0 && lhalf == 0) {
 #pragma unroll
       for (int bj = 0; bj < 2; ++bj) {
@@ -334,6 +341,7 @@ __global__ __launch_bounds__(kThreads) void masked_logits_kernel(const KernelPar
         p.part_i[slot] = run_i[bj];
       }
     }
+    __syncthreads();  // the scratch is read before the next unit's copies may overwrite it
   }
 }
 
@@ -393,17 +401,10 @@ int launch_masked_logits(const LogitsArgs& a, const mosaic_plan& plan, hipStream
     const int64_t tiles = (cap + kTileRows - 1) / kTileRows;
     int64_t grid = tiles * plan.vocab_splits;
     if (grid > plan.grid) grid = plan.grid;
-    switch (variant) {
-      case 1:
-        hipLaunchKernelGGL((masked_logits_kernel<2, 0>), dim3((unsigned)grid), dim3(kThreads), 0, stream, p);
-        break;
-      case 2:
-        hipLaunchKernelGGL((masked_logits_kernel<2, 2>), dim3((unsigned)grid), dim3(kThreads), 0, stream, p);
-        break;
-      default:
-        hipLaunchKernelGGL((masked_logits_kernel<2, 1>), dim3((unsigned)grid), dim3(kThreads), 0, stream, p);
-        break;
-    }
+    if (variant == 1)  // tuning/debug: two slots per operand, 128 KiB of LDS
+      hipLaunchKernelGGL((masked_logits_kernel<2, 2>), dim3((unsigned)grid), dim3(kThreads), 0, stream, p);
+    else
+      hipLaunchKernelGGL((masked_logits_kernel<3, 2>), dim3((unsigned)grid), dim3(kThreads), 0, stream, p);
     hipLaunchKernelGGL(combine_kernel, dim3((unsigned)((cap + 255) / 256)), dim3(256), 0, stream, p);
   }
   return hipGetLastError() == hipSuccess ? 0 : -1;

@@ -61,7 +61,7 @@ extern "C" int mosaic_plan_workspace(int64_t T, int64_t max_rows, int32_t d, int
       out_plan->num_chunks = (int32_t)((rows + C - 1) / C);  // chunks that actually hold rows
       out_plan->rows_per_chunk = (int32_t)C;
       out_plan->vocab_splits = (int32_t)S;
-      out_plan->tile_panel = (int32_t)(row_tiles <= 16 ? row_tiles : 8);
+      out_plan->tile_panel = (int32_t)(row_tiles <= 8 ? row_tiles : 8);
       int64_t grid = row_tiles * S;
       if (grid > num_cus) grid = num_cus;
       out_plan->grid = (int32_t)grid;
