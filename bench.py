@@ -90,7 +90,7 @@ def main():
         "pct_bf16_mfma_peak": 100.0 * flop / sec_per_step / 1e12 / PEAK_BF16_TFLOPS,
         "peak_workspace_bytes": op.workspace_bytes,
         "logits_bytes_avoided": {"fp32_MxV": 4 * M * wl.V, "fp32_TxV": 4 * wl.T * wl.V},
-        "roofline": {"bound": "mfma", "kernel": "masked_logits_kernel", "achieved": tflops,
+        "roofline": {"bound": "mfma", "kernel": "masked_logits_kernel_w4", "achieved": tflops,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": tflops / PEAK_BF16_TFLOPS,
                      "kernel_ms": kern_ms, "flop_per_launch": flop, "traffic": None},
     }

@@ -53,7 +53,7 @@ const char *mosaic_status_string(int status);
 #define MOSAIC_MAX_VOCAB_SPLITS 64
 
 /* Result of the chunk-size selector.  All fields are filled by mosaic_plan_workspace;
- * callers may read them but should not edit them. */
+ * callers may read them and may set `flags`, nothing else. */
 typedef struct {
   int64_t workspace_bytes; /* bytes mosaic_masked_logits_reduce needs in `workspace`    */
   int32_t num_chunks;      /* K_logits: number of sequential chunks over masked rows    */
@@ -61,8 +61,13 @@ typedef struct {
   int32_t vocab_splits;    /* S: vocabulary ranges whose partial results are merged     */
   int32_t tile_panel;      /* row tiles scheduled side by side (cache-sharing group)    */
   int32_t grid;            /* persistent workgroups launched per chunk                  */
-  int32_t reserved;
+  int32_t flags;           /* 0, or MOSAIC_PLAN_GENERAL_KERNEL (see below)                */
 } mosaic_plan;
+
+/* plan.flags bit: use the general 8-wave kernel even where the hand-scheduled 4-wave kernel applies
+ * (it applies when V is a multiple of MOSAIC_VOCAB_TILE and hidden spans less than 4 GiB).  Both give
+ * the same results; the flag exists for testing and tuning. */
+#define MOSAIC_PLAN_GENERAL_KERNEL 1
 
 /*
  * Chunk-size selector (paper section 4.4, "lazy chunking strategy" and "online

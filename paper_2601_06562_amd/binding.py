@@ -23,6 +23,7 @@ MOSAIC_ERR_HIP = -4
 ROW_TILE = 256
 VOCAB_TILE = 256
 K_TILE = 64
+PLAN_GENERAL_KERNEL = 1   # plan.flags bit: force the general 8-wave kernel
 
 EXPORTS = (
     "mosaic_status_string", "mosaic_plan_workspace", "mosaic_compact_scratch_bytes", "mosaic_mask_compact",
@@ -38,7 +39,7 @@ class MosaicPlan(ctypes.Structure):
         ("vocab_splits", ctypes.c_int32),
         ("tile_panel", ctypes.c_int32),
         ("grid", ctypes.c_int32),
-        ("reserved", ctypes.c_int32),
+        ("flags", ctypes.c_int32),
     ]
 
     def __repr__(self):

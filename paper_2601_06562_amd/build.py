@@ -3,6 +3,7 @@ from __future__ import annotations
 
 import os
 import subprocess
+import sys
 
 PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
@@ -19,6 +20,9 @@ FLAGS = [
 
 
 def build_library(verbose: bool = False) -> str:
+    # the hand-scheduled K-loop of the 4-wave kernel is generated text; regenerate it so it cannot go stale
+    subprocess.run([sys.executable, os.path.join(CSRC, "gen_w4_loop.py")], check=True,
+                   stdout=None if verbose else subprocess.DEVNULL)
     cmd = [HIPCC, *FLAGS, "-I" + os.path.join(ROOT, "include"), "-I" + CSRC, "-o", LIB,
            *[os.path.join(CSRC, s) for s in SOURCES]]
     if verbose:

@@ -1,0 +1,236 @@
+#!/usr/bin/env python3
+"""Generates mosaic_w4_loop.inc: the hand-scheduled K-loop of the 4-wave fused kernel as one inline-asm statement.
+
+One statement = the nk K-tiles of one vocabulary tile.  Per K-tile (step g) a wave issues 64 MFMAs in four
+groups of 16; between the MFMAs of a group sit the 8 ds_read_b128 of the next group's fragments and up to 4
+direct-to-LDS copies, so that nothing but MFMAs is ever waited on in steady state.
+"""
+import sys
+
+FA = [[f"v[{180 + 32 * b + 4 * i}:{183 + 32 * b + 4 * i}]" for i in range(4)] for b in range(2)]
+FB = [[f"v[{196 + 32 * b + 4 * j}:{199 + 32 * b + 4 * j}]" for j in range(4)] for b in range(2)]
+VT0, VT1 = "v244", "v245"
+WSRC, HSRC = "s[96:97]", "s[98:99]"
+KT = "s95"
+
+lines = []
+uid = [0]
+
+
+def e(s):
+    lines.append(s)
+
+
+def label(name):
+    uid[0] += 1
+    return f"L{name}{uid[0]}_%="
+
+
+def mfma(bi, bj, buf):
+    e(f"v_mfma_f32_32x32x16_bf16 %[a{bi}{bj}], {FA[buf][bi]}, {FB[buf][bj]}, %[a{bi}{bj}]")
+
+
+def read_addr(ks):
+    e(f"v_add_u32 {VT0}, %[wrd], %[rdw{ks}]")
+    e(f"v_add_u32 {VT1}, %[hrd], %[rdh{ks}]")
+
+
+def reads(buf):
+    out = []
+    for i in range(4):
+        off = f" offset:{4096 * i}" if i else ""
+        out.append(f"ds_read_b128 {FA[buf][i]}, {VT0}{off}")
+    for j in range(4):
+        off = f" offset:{4096 * j}" if j else ""
+        out.append(f"ds_read_b128 {FB[buf][j]}, {VT1}{off}")
+    return out
+
+
+def dma_w(i):
+    return [f"s_add_u32 m0, %[wdst], {1024 * i}", "s_nop 0", f"global_load_lds_dwordx4 %[woff{i}], {WSRC}"]
+
+
+def dma_h(i):
+    return [f"s_add_u32 m0, %[hdst], {98304 + 1024 * i}", "s_nop 0", f"global_load_lds_dwordx4 %[hoff{i}], {HSRC}"]
+
+
+def advance_h():
+    wrap, done = label("hwrap"), label("hdone")
+    e("s_add_u32 %[hk], %[hk], 1")
+    e("s_cmp_eq_u32 %[hk], %[nk]")
+    e(f"s_cbranch_scc1 {wrap}")
+    e("s_add_u32 s98, s98, 128")
+    e("s_addc_u32 s99, s99, 0")
+    e(f"s_branch {done}")
+    e(f"{wrap}:")
+    e("s_mov_b32 %[hk], 0")
+    e("s_sub_u32 s98, s98, %[hwrap]")
+    e("s_subb_u32 s99, s99, 0")
+    e(f"{done}:")
+    e("s_xor_b32 %[hdst], %[hdst], 0x8000")
+
+
+def advance_w():
+    wrap, done, nowrap = label("wwrap"), label("wdone"), label("wslot")
+    e("s_add_u32 %[wk], %[wk], 1")
+    e("s_cmp_eq_u32 %[wk], %[nk]")
+    e(f"s_cbranch_scc1 {wrap}")
+    e("s_add_u32 s96, s96, 128")
+    e("s_addc_u32 s97, s97, 0")
+    e(f"s_branch {done}")
+    e(f"{wrap}:")
+    e("s_mov_b32 %[wk], 0")
+    e("s_add_u32 s96, s96, %[wwrap]")
+    e("s_addc_u32 s97, s97, 0")
+    e(f"{done}:")
+    e("s_add_u32 %[wdst], %[wdst], 0x8000")
+    e("s_cmp_ge_u32 %[wdst], 0x18000")
+    e(f"s_cbranch_scc0 {nowrap}")
+    e("s_sub_u32 %[wdst], %[wdst], 0x18000")
+    e(f"{nowrap}:")
+
+
+def cond_g_ge1_and(plus):
+    """scc = (g >= 1) && (g + plus < total)"""
+    e(f"s_add_u32 vcc_lo, %[g], {plus}")
+    e("s_cmp_lt_u32 vcc_lo, %[total]")
+    e("s_cselect_b32 vcc_lo, 1, 0")
+    e("s_cmp_ge_u32 %[g], 1")
+    e("s_cselect_b32 vcc_hi, 1, 0")
+    e("s_and_b32 vcc_lo, vcc_lo, vcc_hi")
+
+
+def cond_plus(plus):
+    """scc = (g + plus < total)"""
+    e(f"s_add_u32 vcc_lo, %[g], {plus}")
+    e("s_cmp_lt_u32 vcc_lo, %[total]")
+
+
+def group(buf, rd=None, dma=None, cond=None, after=None):
+    """16 MFMAs on fragment buffer `buf`.  rd = list of 8 ds_reads slotted after MFMAs 0..7.
+    dma = list of 4 copy sequences slotted after MFMAs 8..11, guarded by `cond` (emits scc); `after` runs
+    once the copies are out (state advance)."""
+    e("s_waitcnt lgkmcnt(0)")
+    order = [(bi, bj) for bi in range(4) for bj in range(4)]
+    for k in range(8):
+        mfma(*order[k], buf)
+        if rd:
+            e(rd[k])
+    if dma:
+        skip, join = label("nodma"), label("join")
+        cond()
+        e(f"s_cbranch_scc0 {skip}")
+        for k in range(8, 12):
+            mfma(*order[k], buf)
+            for s in dma[k - 8]:
+                e(s)
+        if after:
+            after()
+        e(f"s_branch {join}")
+        e(f"{skip}:")
+        for k in range(8, 12):
+            mfma(*order[k], buf)
+        e(f"{join}:")
+    else:
+        for k in range(8, 12):
+            mfma(*order[k], buf)
+    for k in range(12, 16):
+        mfma(*order[k], buf)
+
+
+def build():
+    # entry: pointers into fixed SGPR pairs, first fragments of the current step
+    e("s_mov_b32 s96, %[wsrc_lo]")
+    e("s_mov_b32 s97, %[wsrc_hi]")
+    e("s_mov_b32 s98, %[hsrc_lo]")
+    e("s_mov_b32 s99, %[hsrc_hi]")
+    e(f"s_mov_b32 {KT}, 0")
+    read_addr(0)
+    for r in reads(0):
+        e(r)
+    e("s_nop 7")
+    step = label("step")
+    e(f"{step}:")
+    # ks0: MFMAs on buffer 0, fragments of ks1 -> buffer 1, second half of the hidden copies (tile g+1)
+    read_addr(1)
+    group(0, rd=reads(1), dma=[dma_h(4 + i) for i in range(4)], cond=lambda: cond_g_ge1_and(1), after=advance_h)
+    # ks1: buffer 1, fragments ks2 -> buffer 0, first half of the LM-head copies (tile g+2)
+    read_addr(2)
+    group(1, rd=reads(0), dma=[dma_w(i) for i in range(4)], cond=lambda: cond_g_ge1_and(2))
+    # ks2: buffer 0, fragments ks3 -> buffer 1, second half of the LM-head copies
+    read_addr(3)
+    group(0, rd=reads(1), dma=[dma_w(4 + i) for i in range(4)], cond=lambda: cond_g_ge1_and(2), after=advance_w)
+    # sync (if a next step exists)
+    nosync, stepend = label("nosync"), label("stepend")
+    cond_plus(1)
+    e(f"s_cbranch_scc0 {nosync}")
+    e("s_waitcnt lgkmcnt(0)")
+    w0, wd = label("wait0"), label("waited")
+    cond_g_ge1_and(2)
+    e(f"s_cbranch_scc0 {w0}")
+    e("s_waitcnt vmcnt(8)")
+    e(f"s_branch {wd}")
+    e(f"{w0}:")
+    e("s_waitcnt vmcnt(0)")
+    e(f"{wd}:")
+    e("s_barrier")
+    nowrap = label("rdslot")
+    e("s_add_u32 %[wrd], %[wrd], 0x8000")
+    e("s_cmp_ge_u32 %[wrd], 0x18000")
+    e(f"s_cbranch_scc0 {nowrap}")
+    e("s_mov_b32 %[wrd], 0")
+    e(f"{nowrap}:")
+    e("s_xor_b32 %[hrd], %[hrd], 0x8000")
+    # ks3: buffer 1, fragments of the next step's ks0 -> buffer 0, first half of the hidden copies (tile g+2)
+    read_addr(0)
+    group(1, rd=reads(0), dma=[dma_h(i) for i in range(4)], cond=lambda: cond_plus(2))
+    e(f"s_branch {stepend}")
+    e(f"{nosync}:")
+    group(1)
+    e(f"{stepend}:")
+    e("s_add_u32 %[g], %[g], 1")
+    e(f"s_add_u32 {KT}, {KT}, 1")
+    e(f"s_cmp_lt_u32 {KT}, %[nk]")
+    e(f"s_cbranch_scc1 {step}")
+    # exit: results visible to the VALU, pointers back to the operands
+    e("s_nop 15")
+    e("s_nop 15")
+    e("s_mov_b32 %[wsrc_lo], s96")
+    e("s_mov_b32 %[wsrc_hi], s97")
+    e("s_mov_b32 %[hsrc_lo], s98")
+    e("s_mov_b32 %[hsrc_hi], s99")
+
+
+def main(path):
+    build()
+    outs = [f'[a{bi}{bj}] "+a"(acc[{bi}][{bj}])' for bi in range(4) for bj in range(4)]
+    for name in ("wsrc_lo", "wsrc_hi", "hsrc_lo", "hsrc_hi", "wrd", "hrd", "wdst", "hdst", "wk", "hk", "g"):
+        outs.append(f'[{name}] "+s"(st_{name})')
+    ins = []
+    for k in range(4):
+        ins.append(f'[rdw{k}] "v"(rdw[{k}])')
+    for k in range(4):
+        ins.append(f'[rdh{k}] "v"(rdh[{k}])')
+    for i in range(8):
+        ins.append(f'[woff{i}] "v"(woff[{i}])')
+    for i in range(8):
+        ins.append(f'[hoff{i}] "v"(hoff[{i}])')
+    for name in ("total", "nk", "wwrap", "hwrap"):
+        ins.append(f'[{name}] "s"(st_{name})')
+    clob = [f'"v{r}"' for r in range(180, 246)] + ['"s95"', '"s96"', '"s97"', '"s98"', '"s99"', '"vcc"', '"scc"', '"m0"',
+                                                     '"memory"']
+    with open(path, "w") as f:
+        f.write("// GENERATED by gen_w4_loop.py -- do not edit.  The K-loop of one vocabulary tile (4-wave kernel).\n")
+        f.write("asm volatile(\n")
+        for ln in lines:
+            f.write(f'    "{ln}\\n"\n')
+        f.write("    : " + ",\n      ".join(outs) + "\n")
+        f.write("    : " + ",\n      ".join(ins) + "\n")
+        f.write("    : " + ", ".join(clob) + ");\n")
+    print(f"{path}: {len(lines)} asm lines, {len(outs) + len(ins)} operands")
+
+
+if __name__ == "__main__":
+    import os
+    main(sys.argv[1] if len(sys.argv) > 1 else os.path.join(os.path.dirname(os.path.abspath(__file__)),
+                                                            "mosaic_w4_loop.inc"))

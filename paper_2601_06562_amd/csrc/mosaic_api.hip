@@ -63,6 +63,7 @@ int mosaic_masked_logits_reduce(const void* hidden, int64_t T, int32_t d, int64_
 
   mosaic::LogitsArgs a;
   a.hidden = hidden;
+  a.T = T;
   a.ld_h = ld_h;
   a.w = w;
   a.d = d;

@@ -17,6 +17,7 @@ int launch_compact(const uint8_t* mask, int64_t T, int32_t* out_idx, int32_t* ou
 // ---- fused gather-GEMM + vocabulary reduction (mosaic_logits.hip)
 struct LogitsArgs {
   const void* hidden;   // bf16 [T, ld_h]
+  int64_t T;            // rows of hidden
   int64_t ld_h;         // elements
   const void* w;        // bf16 [V, d]
   int32_t d;

@@ -345,6 +345,244 @@ __global__ __launch_bounds__(kThreads) void masked_logits_kernel(const KernelPar
   }
 }
 
+// Same reduction for the 4-wave kernel: this wave's 128 vocabulary ids x 128 tokens (4 token columns).
+template <bool TAIL>
+__device__ __forceinline__ void reduce_tile4(f32x16 (&acc)[4][4], float (&m)[4], float (&s)[4], int (&ix)[4], int vb,
+                                             int V) {
+#pragma unroll
+  for (int bj = 0; bj < 4; ++bj) {
+    float mt = kNeg;
+#pragma unroll
+    for (int bi = 0; bi < 4; ++bi) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int code = bi * 32 + 8 * (r >> 2) + (r & 3);
+        if (TAIL) {
+          if (vb + code >= V) acc[bi][bj][r] = kNeg;
+        }
+        mt = fmaxf(mt, acc[bi][bj][r]);
+      }
+    }
+    int sel = 0;
+#pragma unroll
+    for (int bi = 3; bi >= 0; --bi) {
+#pragma unroll
+      for (int r = 15; r >= 0; --r) {
+        const int code = bi * 32 + 8 * (r >> 2) + (r & 3);
+        sel = (acc[bi][bj][r] == mt) ? code : sel;
+      }
+    }
+    const bool upd = mt > m[bj];
+    ix[bj] = upd ? vb + sel : ix[bj];
+    const float mn = fmaxf(m[bj], mt);
+    const float nml = -mn * kLog2e;
+    float p0 = 0.f, p1 = 0.f, p2 = 0.f, p3 = 0.f;
+#pragma unroll
+    for (int bi = 0; bi < 4; ++bi) {
+#pragma unroll
+      for (int r = 0; r < 16; r += 4) {
+        p0 += exp_rel<TAIL>(acc[bi][bj][r + 0], mn, nml);
+        p1 += exp_rel<TAIL>(acc[bi][bj][r + 1], mn, nml);
+        p2 += exp_rel<TAIL>(acc[bi][bj][r + 2], mn, nml);
+        p3 += exp_rel<TAIL>(acc[bi][bj][r + 3], mn, nml);
+      }
+    }
+    s[bj] = s[bj] * __builtin_amdgcn_exp2f((m[bj] - mn) * kLog2e) + ((p0 + p1) + (p2 + p3));
+    m[bj] = mn;
+    __builtin_amdgcn_sched_barrier(0);  // keep one token column's 64 logits live at a time
+  }
+}
+
+// ---- 4-wave fast path: one wave per SIMD, 128 (vocab) x 128 (token) per wave, accumulators in AGPRs.
+// The K-loop of a vocabulary tile is one hand-scheduled inline-asm statement (w4_loop.inc, generated):
+// every MFMA is followed by at most one LDS read or one direct-to-LDS copy, fragments are double-
+// buffered in fixed VGPRs, the LM-head ring runs two K-tiles ahead and the hidden ring one.
+// Preconditions (checked by the launcher): V % 256 == 0, hidden span < 4 GiB, 256*d*2 < 4 GiB.
+__global__ __launch_bounds__(256) void masked_logits_kernel_w4(const KernelParams p) {
+  constexpr int NW = 3, NH = 2;
+  constexpr int kTileK = 64;
+  constexpr int kRowBytes = 128;
+  constexpr int kOperandBytes = 256 * kRowBytes;        // 32 KiB
+  constexpr int kSwzShift = 1;
+  __shared__ __attribute__((aligned(1024))) char smem[(NW + NH) * kOperandBytes];
+  float* red_m = reinterpret_cast<float*>(smem);        // merge scratch aliases W slot 0 at unit end
+  float* red_s = red_m + 256;
+  int* red_i = reinterpret_cast<int*>(red_s + 256);
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wv = wave & 1;   // vocabulary half of the tile
+  const int wt = wave >> 1;  // token half of the tile
+  const int l32 = lane & 31, lhalf = lane >> 5;
+
+  int total = *p.count;
+  if (total > p.max_rows) total = p.max_rows;
+  int rows = total - p.row0;
+  if (rows > p.chunk_rows) rows = p.chunk_rows;
+  if (rows <= 0) return;
+  const int n_tt = (rows + kTileRows - 1) / kTileRows;
+
+  const int G = gridDim.x;
+  int pos = blockIdx.x;
+  if ((G & 7) == 0) pos = (int)(blockIdx.x & 7) * (G >> 3) + (int)(blockIdx.x >> 3);
+  const int S = p.splits;
+  const int n_units = n_tt * S;
+  const int A = p.panel < n_tt ? p.panel : n_tt;
+  const int full_panel_units = A * S;
+  const int n_panels = (n_tt + A - 1) / A;
+
+  // Direct-to-LDS copy: instruction i (0..7) of this wave fills rows wave*64 + 8*i + lane/8; the swizzle
+  // of row drow + 8*i depends on i only through its parity.
+  const int drow = wave * 64 + (lane >> 3);
+  const uint32_t chunk_even = (uint32_t)(((lane & 7) ^ ((drow >> kSwzShift) & 7)) * 16);
+  const uint32_t chunk_odd = (uint32_t)(((lane & 7) ^ (((drow + 8) >> kSwzShift) & 7)) * 16);
+  const int nk = p.d / kTileK;
+  const uint32_t w_row_bytes = (uint32_t)p.d * 2u;
+
+  // LDS read offsets per K sub-step: row (lane%32) of this wave's first 32-row block, swizzled chunk.
+  uint32_t rdw[4], rdh[4], woff[8];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) {
+    const uint32_t o = (uint32_t)(l32 * kRowBytes + (((2 * ks + lhalf) ^ ((l32 >> kSwzShift) & 7)) * 16));
+    rdw[ks] = o + (uint32_t)(wv * 128 * kRowBytes);
+    rdh[ks] = o + (uint32_t)(NW * kOperandBytes + wt * 128 * kRowBytes);
+  }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) woff[i] = (uint32_t)(drow + 8 * i) * w_row_bytes + ((i & 1) ? chunk_odd : chunk_even);
+
+  const uint32_t u_nk = (uint32_t)nk;
+  const uint32_t u_wwrap = 256u * w_row_bytes - (uint32_t)(nk - 1) * 128u;
+  const uint32_t u_hwrap = (uint32_t)(nk - 1) * 128u;
+  const uint32_t wave_dst = (uint32_t)wave * 64u * kRowBytes;
+
+  for (int u = pos; u < n_units; u += G) {
+    int pnl = u / full_panel_units;
+    if (pnl >= n_panels) pnl = n_panels - 1;
+    const int ul = u - pnl * full_panel_units;
+    const int hp = (n_tt - pnl * A) < A ? (n_tt - pnl * A) : A;
+    const int sp = ul / hp;
+    const int tt = pnl * A + ul % hp;
+    const int vt0 = (int)(((int64_t)sp * p.vocab_tiles) / S);
+    const int vt1 = (int)(((int64_t)(sp + 1) * p.vocab_tiles) / S);
+    const int ntile = vt1 - vt0;
+    const int total_steps = ntile * nk;
+    const uint32_t u_total = (uint32_t)total_steps;
+
+    // Gather: 32-bit byte offsets of the 8 hidden rows this lane copies (rows past the end of the chunk
+    // re-read the last valid row; their results are never stored).
+    uint32_t hoff[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      int j = tt * kTileRows + drow + 8 * i;
+      if (j > rows - 1) j = rows - 1;
+      const int t = p.idx[p.row0 + j];
+      hoff[i] = (uint32_t)t * (uint32_t)p.ldh_bytes + ((i & 1) ? chunk_odd : chunk_even);
+    }
+
+    // Prologue copies, in this order: W0, H0, W1, W2, H1 (tile 0 is needed first, H1 at the first sync).
+    auto copy_w = [&](int gw) {
+      const char* src = p.w + ((int64_t)(vt0 + gw / nk) * kTileVocab) * (int64_t)w_row_bytes + (gw % nk) * kRowBytes;
+      char* dst = smem + (gw % NW) * kOperandBytes + wave_dst;
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        __builtin_amdgcn_global_load_lds((gbl_ptr_t)(src + woff[i]), (lds_ptr_t)(dst + i * 1024), 16, 0, 0);
+    };
+    auto copy_h = [&](int gh) {
+      const char* src = p.hidden + (gh % nk) * kRowBytes;
+      char* dst = smem + (NW + gh % NH) * kOperandBytes + wave_dst;
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        __builtin_amdgcn_global_load_lds((gbl_ptr_t)(src + hoff[i]), (lds_ptr_t)(dst + i * 1024), 16, 0, 0);
+    };
+    wait_vm<0>();
+    copy_w(0);
+    copy_h(0);
+    int after0 = 0;
+    if (1 < total_steps) { copy_w(1); after0 += 1; }
+    if (2 < total_steps) { copy_w(2); after0 += 1; }
+    if (1 < total_steps) { copy_h(1); after0 += 1; }
+    if (after0 == 3) wait_vm<24>(); else if (after0 == 2) wait_vm<16>(); else if (after0 == 1) wait_vm<8>(); else wait_vm<0>();
+    __builtin_amdgcn_s_barrier();
+
+    // State of the asm loop: next tiles to copy are W(3) and H(2) (never issued if past the end).
+    const int gw = 3, gh = 2;
+    const uint64_t wsrc0 = (uint64_t)(p.w + ((int64_t)(vt0 + gw / nk) * kTileVocab) * (int64_t)w_row_bytes + (gw % nk) * kRowBytes);
+    const uint64_t hsrc0 = (uint64_t)(p.hidden + (gh % nk) * kRowBytes);
+    uint32_t st_wsrc_lo = (uint32_t)wsrc0, st_wsrc_hi = (uint32_t)(wsrc0 >> 32);
+    uint32_t st_hsrc_lo = (uint32_t)hsrc0, st_hsrc_hi = (uint32_t)(hsrc0 >> 32);
+    uint32_t st_wrd = 0, st_hrd = 0;
+    uint32_t st_wdst = (uint32_t)((gw % NW) * kOperandBytes) + wave_dst;
+    uint32_t st_hdst = (uint32_t)((gh % NH) * kOperandBytes) + wave_dst;
+    uint32_t st_wk = (uint32_t)(gw % nk), st_hk = (uint32_t)(gh % nk);
+    uint32_t st_g = 0;
+
+    float run_m[4] = {kNeg, kNeg, kNeg, kNeg};
+    float run_s[4] = {0.f, 0.f, 0.f, 0.f};
+    int run_i[4] = {INT_MAX, INT_MAX, INT_MAX, INT_MAX};
+
+    for (int n = 0; n < ntile; ++n) {
+      f32x16 acc[4][4];
+#pragma unroll
+      for (int bi = 0; bi < 4; ++bi)
+#pragma unroll
+        for (int bj = 0; bj < 4; ++bj)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc[bi][bj][r] = 0.f;
+      st_wsrc_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)st_wsrc_lo);
+      st_wsrc_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)st_wsrc_hi);
+      st_hsrc_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)st_hsrc_lo);
+      st_hsrc_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)st_hsrc_hi);
+      st_wrd = (uint32_t)__builtin_amdgcn_readfirstlane((int)st_wrd);
+      st_hrd = (uint32_t)__builtin_amdgcn_readfirstlane((int)st_hrd);
+      st_wdst = (uint32_t)__builtin_amdgcn_readfirstlane((int)st_wdst);
+      st_hdst = (uint32_t)__builtin_amdgcn_readfirstlane((int)st_hdst);
+      st_wk = (uint32_t)__builtin_amdgcn_readfirstlane((int)st_wk);
+      st_hk = (uint32_t)__builtin_amdgcn_readfirstlane((int)st_hk);
+      st_g = (uint32_t)__builtin_amdgcn_readfirstlane((int)st_g);
+      {
+      const uint32_t st_total = (uint32_t)__builtin_amdgcn_readfirstlane((int)u_total);
+      const uint32_t st_nk = (uint32_t)__builtin_amdgcn_readfirstlane((int)u_nk);
+      const uint32_t st_wwrap = (uint32_t)__builtin_amdgcn_readfirstlane((int)u_wwrap);
+      const uint32_t st_hwrap = (uint32_t)__builtin_amdgcn_readfirstlane((int)u_hwrap);
+#include "mosaic_w4_loop.inc"
+      }
+      const int v_tile0 = (vt0 + n) * kTileVocab;
+      const int vb = v_tile0 + wv * 128 + 4 * lhalf;
+      reduce_tile4<false>(acc, run_m, run_s, run_i, vb, p.V);
+    }
+
+#pragma unroll
+    for (int bj = 0; bj < 4; ++bj) {
+      const float m2 = __shfl_xor(run_m[bj], 32, 64);
+      const float s2 = __shfl_xor(run_s[bj], 32, 64);
+      const int i2 = __shfl_xor(run_i[bj], 32, 64);
+      merge_triple(run_m[bj], run_s[bj], run_i[bj], m2, s2, i2);
+    }
+    __syncthreads();  // every wave is done with the ring (the merge scratch aliases it)
+    if (wv == 1 && lhalf == 0) {
+#pragma unroll
+      for (int bj = 0; bj < 4; ++bj) {
+        const int e = (wt * 4 + bj) * 32 + l32;
+        red_m[e] = run_m[bj];
+        red_s[e] = run_s[bj];
+        red_i[e] = run_i[bj];
+      }
+    }
+    __syncthreads();
+    if (wv == 0 && lhalf == 0) {
+#pragma unroll
+      for (int bj = 0; bj < 4; ++bj) {
+        const int e = (wt * 4 + bj) * 32 + l32;
+        merge_triple(run_m[bj], run_s[bj], run_i[bj], red_m[e], red_s[e], red_i[e]);
+        const int64_t slot = (int64_t)sp * p.c_pad + tt * kTileRows + e;
+        p.part_m[slot] = run_m[bj];
+        p.part_s[slot] = run_s[bj];
+        p.part_i[slot] = run_i[bj];
+      }
+    }
+    __syncthreads();
+  }
+}
+
 // Merge the S partial triples of every row in ascending split order and emit the outputs.
 __global__ __launch_bounds__(256) void combine_kernel(const KernelParams p) {
   int total = *p.count;
@@ -364,13 +602,8 @@ __global__ __launch_bounds__(256) void combine_kernel(const KernelParams p) {
   p.out_conf[p.row0 + r] = 1.0f / s;
 }
 
-static int variant_from_env() {
-  const char* e = getenv("MOSAIC_KERNEL_VARIANT");
-  return e ? atoi(e) : 0;
-}
 
 int launch_masked_logits(const LogitsArgs& a, const mosaic_plan& plan, hipStream_t stream) {
-  static const int variant = variant_from_env();
   KernelParams p;
   p.hidden = static_cast<const char*>(a.hidden);
   p.ldh_bytes = a.ld_h * 2;
@@ -392,6 +625,11 @@ int launch_masked_logits(const LogitsArgs& a, const mosaic_plan& plan, hipStream
   p.out_conf = a.out_conf;
   p.out_lse = a.out_lse;
 
+  // The hand-scheduled 4-wave kernel needs whole vocabulary tiles and 32-bit row offsets; everything
+  // else (and plans that ask for it) goes to the general 8-wave kernel.
+  const bool fast = (plan.flags & MOSAIC_PLAN_GENERAL_KERNEL) == 0 && a.V % kTileVocab == 0 &&
+                    (uint64_t)a.T * (uint64_t)p.ldh_bytes < ((uint64_t)1 << 32) &&
+                    (uint64_t)kTileVocab * (uint64_t)a.d * 2u < ((uint64_t)1 << 32);
   for (int c = 0; c < plan.num_chunks; ++c) {
     const int64_t row0 = (int64_t)c * plan.rows_per_chunk;
     if (row0 >= a.max_rows) break;
@@ -401,8 +639,8 @@ int launch_masked_logits(const LogitsArgs& a, const mosaic_plan& plan, hipStream
     const int64_t tiles = (cap + kTileRows - 1) / kTileRows;
     int64_t grid = tiles * plan.vocab_splits;
     if (grid > plan.grid) grid = plan.grid;
-    if (variant == 1)  // tuning/debug: two slots per operand, 128 KiB of LDS
-      hipLaunchKernelGGL((masked_logits_kernel<2, 2>), dim3((unsigned)grid), dim3(kThreads), 0, stream, p);
+    if (fast)
+      hipLaunchKernelGGL(masked_logits_kernel_w4, dim3((unsigned)grid), dim3(256), 0, stream, p);
     else
       hipLaunchKernelGGL((masked_logits_kernel<3, 2>), dim3((unsigned)grid), dim3(kThreads), 0, stream, p);
     hipLaunchKernelGGL(combine_kernel, dim3((unsigned)((cap + 255) / 256)), dim3(256), 0, stream, p);

@@ -65,7 +65,7 @@ extern "C" int mosaic_plan_workspace(int64_t T, int64_t max_rows, int32_t d, int
       int64_t grid = row_tiles * S;
       if (grid > num_cus) grid = num_cus;
       out_plan->grid = (int32_t)grid;
-      out_plan->reserved = 0;
+      out_plan->flags = 0;
       return MOSAIC_OK;
     }
     if (C == MOSAIC_ROW_TILE) return MOSAIC_ERR_WORKSPACE_TOO_SMALL;  // nothing left to chunk

@@ -64,6 +64,13 @@ SMALL = [
     (1024, 256, 2048, 1.0),
     (2000, 64, 5000, 0.4),
     (900, 448, 4099, 0.7),
+    # vocabulary a multiple of 256: the hand-scheduled 4-wave kernel (1, 2, 3, 5, 8 K-tiles; 1..n vocab tiles)
+    (300, 64, 256, 1.0),
+    (520, 128, 512, 0.7),
+    (700, 192, 768, 1.0),
+    (1000, 320, 1280, 0.5),
+    (130, 512, 2560, 1.0),
+    (2100, 64, 4096, 0.9),
 ]
 
 
@@ -203,6 +210,22 @@ def test_chunking_is_a_bitwise_noop_and_deterministic():
         assert out["op"].plan.num_chunks >= 2
         for k in ("tok", "conf", "lse"):
             assert np.array_equal(base[k][:M], out[k][:M]), (K, k)
+
+
+def test_fast_and_general_kernels_agree_bitwise():
+    """Where both kernels apply they run the same MFMA sequence per logit and the same reduction order,
+    so their outputs must be identical, ragged last row tile included."""
+    print("fast vs general kernel", flush=True)
+    for (T, d, V, p) in [(1300, 256, 2048, 0.8), (257, 64, 256, 1.0), (600, 448, 1024, 0.33)]:
+        wl = workloads.small_random(T, d, V, p=p, seed=T, device=DEV)
+        fast = run_hip(wl.hidden, wl.w, wl.mask)
+
+        def general(plan):
+            plan.flags = binding.PLAN_GENERAL_KERNEL
+        gen = run_hip(wl.hidden, wl.w, wl.mask, plan_edit=general)
+        assert gen["op"].plan.flags == 1 and fast["op"].plan.flags == 0
+        for k in ("tok", "conf", "lse"):
+            assert np.array_equal(fast[k], gen[k]), (T, d, V, k)
 
 
 def test_budget_forces_chunks_and_bounds_workspace():
