@@ -28,6 +28,8 @@ def main():
     ap.add_argument("--budget-bytes", type=int, default=0, help="workspace budget for the chunk-size selector")
     ap.add_argument("--cpu-rows", type=int, default=4096, help="rows of the workload the CPU oracle is timed on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run only a plain 1 GiB device-to-device copy (for scaling rocprofv3's FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this path is built and measured on ONE GPU; --gpus N with N > 1 is not supported "
@@ -41,6 +43,14 @@ def main():
     binding.lib()   # fail loudly if the HIP library is not built
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(3)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": True, "bytes_read": 1 << 30, "bytes_written": 1 << 30, "launches": 5}))
+        return
     wl = workloads.make(args.workload, device=dev)
     M = wl.M
     op = MaskOnlyLogits(wl.T, wl.d, wl.V, max_rows=M, budget_bytes=args.budget_bytes, device=dev)
@@ -69,6 +79,12 @@ def main():
     kern_ms = float(np.mean([a.elapsed_time(b) for a, b in events]))   # fused kernel (+ the tiny merge)
 
     flop = 2.0 * M * wl.d * wl.V
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        rec = json.load(open(tpath)).get(args.workload)
+        if rec:
+            traffic = rec["fetch_bytes"] + rec["write_bytes"]   # per launch, rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated
     tflops = flop / (kern_ms * 1e-3) / 1e12
     out = {
         "metric": "masked tokens/sec for mask-only logits (compact + fused gather-GEMM/vocab reduction)",
@@ -92,7 +108,8 @@ def main():
         "logits_bytes_avoided": {"fp32_MxV": 4 * M * wl.V, "fp32_TxV": 4 * wl.T * wl.V},
         "roofline": {"bound": "mfma", "kernel": "masked_logits_kernel_w4", "achieved": tflops,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": tflops / PEAK_BF16_TFLOPS,
-                     "kernel_ms": kern_ms, "flop_per_launch": flop, "traffic": None},
+                     "kernel_ms": kern_ms, "flop_per_launch": flop, "traffic": traffic,
+                     "algorithmic_bytes": 2 * wl.V * wl.d + 2 * M * wl.d + 12 * M},
     }
 
     if not args.no_cpu_baseline:
