@@ -1,14 +1,15 @@
 #!/usr/bin/env python3
 """Generates mosaic_w4_loop.inc: the hand-scheduled K-loop of the 4-wave fused kernel as one inline-asm statement.
 
-One statement = the nk K-tiles of one vocabulary tile.  Per K-tile (step g) a wave issues 64 MFMAs in four
-groups of 16; between the MFMAs of a group sit the 8 ds_read_b128 of the next group's fragments and up to 4
-direct-to-LDS copies, so that nothing but MFMAs is ever waited on in steady state.
+One statement = the nk K-tiles of one vocabulary tile.  Per K-tile (step g) a wave issues 128
+v_mfma_f32_16x16x32_bf16 in two groups of 64 (k 0..31 and k 32..63 of the tile); after every second MFMA
+of a group's first half sits one of the 16 ds_read_b128 that fetch the next group's fragments, then one of
+up to 8 direct-to-LDS copies, so that nothing but MFMAs is ever waited on in steady state.
 """
 import sys
 
-FA = [[f"v[{180 + 32 * b + 4 * i}:{183 + 32 * b + 4 * i}]" for i in range(4)] for b in range(2)]
-FB = [[f"v[{196 + 32 * b + 4 * j}:{199 + 32 * b + 4 * j}]" for j in range(4)] for b in range(2)]
+FA = [[f"v[{116 + 64 * b + 4 * i}:{119 + 64 * b + 4 * i}]" for i in range(8)] for b in range(2)]
+FB = [[f"v[{148 + 64 * b + 4 * j}:{151 + 64 * b + 4 * j}]" for j in range(8)] for b in range(2)]
 VT0, VT1 = "v244", "v245"
 WSRC, HSRC = "s[96:97]", "s[98:99]"
 KT = "s95"
@@ -27,7 +28,7 @@ def label(name):
 
 
 def mfma(bi, bj, buf):
-    e(f"v_mfma_f32_32x32x16_bf16 %[a{bi}{bj}], {FA[buf][bi]}, {FB[buf][bj]}, %[a{bi}{bj}]")
+    e(f"v_mfma_f32_16x16x32_bf16 %[a{bi}{bj}], {FA[buf][bi]}, {FB[buf][bj]}, %[a{bi}{bj}]")
 
 
 def read_addr(ks):
@@ -37,11 +38,11 @@ def read_addr(ks):
 
 def reads(buf):
     out = []
-    for i in range(4):
-        off = f" offset:{4096 * i}" if i else ""
+    for i in range(8):
+        off = f" offset:{2048 * i}" if i else ""
         out.append(f"ds_read_b128 {FA[buf][i]}, {VT0}{off}")
-    for j in range(4):
-        off = f" offset:{4096 * j}" if j else ""
+    for j in range(8):
+        off = f" offset:{2048 * j}" if j else ""
         out.append(f"ds_read_b128 {FB[buf][j]}, {VT1}{off}")
     return out
 
@@ -107,34 +108,35 @@ def cond_plus(plus):
 
 
 def group(buf, rd=None, dma=None, cond=None, after=None):
-    """16 MFMAs on fragment buffer `buf`.  rd = list of 8 ds_reads slotted after MFMAs 0..7.
-    dma = list of 4 copy sequences slotted after MFMAs 8..11, guarded by `cond` (emits scc); `after` runs
+    """64 MFMAs on fragment buffer `buf`.  rd = 16 ds_reads, one after each even MFMA 0..30.
+    dma = 8 copy sequences, one after each even MFMA 32..46, guarded by `cond` (emits scc); `after` runs
     once the copies are out (state advance)."""
     e("s_waitcnt lgkmcnt(0)")
-    order = [(bi, bj) for bi in range(4) for bj in range(4)]
-    for k in range(8):
+    order = [(bi, bj) for bi in range(8) for bj in range(8)]
+    for k in range(32):
         mfma(*order[k], buf)
-        if rd:
-            e(rd[k])
+        if rd and k % 2 == 0:
+            e(rd[k // 2])
     if dma:
         skip, join = label("nodma"), label("join")
         cond()
         e(f"s_cbranch_scc0 {skip}")
-        for k in range(8, 12):
+        for k in range(32, 48):
             mfma(*order[k], buf)
-            for s in dma[k - 8]:
-                e(s)
+            if k % 2 == 0:
+                for x in dma[(k - 32) // 2]:
+                    e(x)
         if after:
             after()
         e(f"s_branch {join}")
         e(f"{skip}:")
-        for k in range(8, 12):
+        for k in range(32, 48):
             mfma(*order[k], buf)
         e(f"{join}:")
     else:
-        for k in range(8, 12):
+        for k in range(32, 48):
             mfma(*order[k], buf)
-    for k in range(12, 16):
+    for k in range(48, 64):
         mfma(*order[k], buf)
 
 
@@ -151,16 +153,11 @@ def build():
     e("s_nop 7")
     step = label("step")
     e(f"{step}:")
-    # ks0: MFMAs on buffer 0, fragments of ks1 -> buffer 1, second half of the hidden copies (tile g+1)
+    # first half (k 0..31): MFMAs on buffer 0, fragments of the second half -> buffer 1, the LM-head copies
+    # of tile g+2 (decided at the previous sync)
     read_addr(1)
-    group(0, rd=reads(1), dma=[dma_h(4 + i) for i in range(4)], cond=lambda: cond_g_ge1_and(1), after=advance_h)
-    # ks1: buffer 1, fragments ks2 -> buffer 0, first half of the LM-head copies (tile g+2)
-    read_addr(2)
-    group(1, rd=reads(0), dma=[dma_w(i) for i in range(4)], cond=lambda: cond_g_ge1_and(2))
-    # ks2: buffer 0, fragments ks3 -> buffer 1, second half of the LM-head copies
-    read_addr(3)
-    group(0, rd=reads(1), dma=[dma_w(4 + i) for i in range(4)], cond=lambda: cond_g_ge1_and(2), after=advance_w)
-    # sync (if a next step exists)
+    group(0, rd=reads(1), dma=[dma_w(i) for i in range(8)], cond=lambda: cond_g_ge1_and(2), after=advance_w)
+    # sync (if a next step exists): every wave holds all fragments of step g in registers
     nosync, stepend = label("nosync"), label("stepend")
     cond_plus(1)
     e(f"s_cbranch_scc0 {nosync}")
@@ -181,9 +178,10 @@ def build():
     e("s_mov_b32 %[wrd], 0")
     e(f"{nowrap}:")
     e("s_xor_b32 %[hrd], %[hrd], 0x8000")
-    # ks3: buffer 1, fragments of the next step's ks0 -> buffer 0, first half of the hidden copies (tile g+2)
+    # second half (k 32..63): buffer 1, fragments of the next step's first half -> buffer 0 (new slots),
+    # the hidden copies of tile g+2
     read_addr(0)
-    group(1, rd=reads(0), dma=[dma_h(i) for i in range(4)], cond=lambda: cond_plus(2))
+    group(1, rd=reads(0), dma=[dma_h(i) for i in range(8)], cond=lambda: cond_plus(2), after=advance_h)
     e(f"s_branch {stepend}")
     e(f"{nosync}:")
     group(1)
@@ -203,13 +201,13 @@ def build():
 
 def main(path):
     build()
-    outs = [f'[a{bi}{bj}] "+a"(acc[{bi}][{bj}])' for bi in range(4) for bj in range(4)]
+    outs = [f'[a{bi}{bj}] "+a"(acc[{bi}][{bj}])' for bi in range(8) for bj in range(8)]
     for name in ("wsrc_lo", "wsrc_hi", "hsrc_lo", "hsrc_hi", "wrd", "hrd", "wdst", "hdst", "wk", "hk", "g"):
         outs.append(f'[{name}] "+s"(st_{name})')
     ins = []
-    for k in range(4):
+    for k in range(2):
         ins.append(f'[rdw{k}] "v"(rdw[{k}])')
-    for k in range(4):
+    for k in range(2):
         ins.append(f'[rdh{k}] "v"(rdh[{k}])')
     for i in range(8):
         ins.append(f'[woff{i}] "v"(woff[{i}])')
@@ -217,7 +215,7 @@ def main(path):
         ins.append(f'[hoff{i}] "v"(hoff[{i}])')
     for name in ("total", "nk", "wwrap", "hwrap"):
         ins.append(f'[{name}] "s"(st_{name})')
-    clob = [f'"v{r}"' for r in range(180, 246)] + ['"s95"', '"s96"', '"s97"', '"s98"', '"s99"', '"vcc"', '"scc"', '"m0"',
+    clob = [f'"v{r}"' for r in range(116, 246)] + ['"s95"', '"s96"', '"s97"', '"s98"', '"s99"', '"vcc"', '"scc"', '"m0"',
                                                      '"memory"']
     with open(path, "w") as f:
         f.write("// GENERATED by gen_w4_loop.py -- do not edit.  The K-loop of one vocabulary tile (4-wave kernel).\n")

@@ -10,9 +10,10 @@
 //
 // Shape of the computation.  The MFMA "A" operand is the LM-head tile (vocabulary ids along the
 // instruction's rows), "B" is the gathered hidden tile (token rows along the instruction's columns).
-// With v_mfma_f32_32x32x16_bf16 a lane then owns ONE token (column lane%32) and 16 vocabulary ids of a
-// 32x32 block, so the reduction over the vocabulary is almost entirely in-register; the only
-// cross-lane step (lane ^ 32) and the cross-wave step happen once per work unit, not per tile.
+// A lane then owns ONE token per accumulator block (column lane%16 with v_mfma_f32_16x16x32_bf16 in the
+// 4-wave kernel, lane%32 with v_mfma_f32_32x32x16_bf16 in the general one) and several vocabulary ids,
+// so the reduction over the vocabulary is almost entirely in-register; the cross-lane steps and the
+// cross-wave step happen once per work unit, not per tile.
 //
 // Work decomposition.  A unit is (row tile of 256 masked tokens, vocabulary split); a workgroup of
 // 8 waves walks the 256-wide vocabulary tiles of its split, carrying the running triple in registers,
@@ -345,55 +346,42 @@ __global__ __launch_bounds__(kThreads) void masked_logits_kernel(const KernelPar
   }
 }
 
-// Same reduction for the 4-wave kernel: this wave's 128 vocabulary ids x 128 tokens (4 token columns).
-template <bool TAIL>
-__device__ __forceinline__ void reduce_tile4(f32x16 (&acc)[4][4], float (&m)[4], float (&s)[4], int (&ix)[4], int vb,
-                                             int V) {
+using f32x4 = __attribute__((ext_vector_type(4))) float;
+
+// Reduction of one finished 256x256 logits tile for the 16x16x32 layout: this lane holds, for each of
+// 8 token columns (tb*16 + lane%16), 8 blocks x 4 vocabulary ids (vb + 16*bi + r).
+__device__ __forceinline__ void reduce_tile16(f32x4 (&acc)[8][8], float (&m)[8], float (&s)[8], int (&ix)[8], int vb) {
 #pragma unroll
-  for (int bj = 0; bj < 4; ++bj) {
+  for (int tb = 0; tb < 8; ++tb) {
     float mt = kNeg;
 #pragma unroll
-    for (int bi = 0; bi < 4; ++bi) {
+    for (int bi = 0; bi < 8; ++bi)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int code = bi * 32 + 8 * (r >> 2) + (r & 3);
-        if (TAIL) {
-          if (vb + code >= V) acc[bi][bj][r] = kNeg;
-        }
-        mt = fmaxf(mt, acc[bi][bj][r]);
-      }
-    }
+      for (int r = 0; r < 4; ++r) mt = fmaxf(mt, acc[bi][tb][r]);
     int sel = 0;
 #pragma unroll
-    for (int bi = 3; bi >= 0; --bi) {
+    for (int bi = 7; bi >= 0; --bi)
 #pragma unroll
-      for (int r = 15; r >= 0; --r) {
-        const int code = bi * 32 + 8 * (r >> 2) + (r & 3);
-        sel = (acc[bi][bj][r] == mt) ? code : sel;
-      }
-    }
-    const bool upd = mt > m[bj];
-    ix[bj] = upd ? vb + sel : ix[bj];
-    const float mn = fmaxf(m[bj], mt);
+      for (int r = 3; r >= 0; --r) sel = (acc[bi][tb][r] == mt) ? (bi * 16 + r) : sel;  // descending: lowest id wins
+    const bool upd = mt > m[tb];
+    ix[tb] = upd ? vb + sel : ix[tb];
+    const float mn = fmaxf(m[tb], mt);
     const float nml = -mn * kLog2e;
     float p0 = 0.f, p1 = 0.f, p2 = 0.f, p3 = 0.f;
 #pragma unroll
-    for (int bi = 0; bi < 4; ++bi) {
-#pragma unroll
-      for (int r = 0; r < 16; r += 4) {
-        p0 += exp_rel<TAIL>(acc[bi][bj][r + 0], mn, nml);
-        p1 += exp_rel<TAIL>(acc[bi][bj][r + 1], mn, nml);
-        p2 += exp_rel<TAIL>(acc[bi][bj][r + 2], mn, nml);
-        p3 += exp_rel<TAIL>(acc[bi][bj][r + 3], mn, nml);
-      }
+    for (int bi = 0; bi < 8; ++bi) {
+      p0 += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[bi][tb][0], kLog2e, nml));
+      p1 += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[bi][tb][1], kLog2e, nml));
+      p2 += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[bi][tb][2], kLog2e, nml));
+      p3 += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[bi][tb][3], kLog2e, nml));
     }
-    s[bj] = s[bj] * __builtin_amdgcn_exp2f((m[bj] - mn) * kLog2e) + ((p0 + p1) + (p2 + p3));
-    m[bj] = mn;
-    __builtin_amdgcn_sched_barrier(0);  // keep one token column's 64 logits live at a time
+    s[tb] = s[tb] * __builtin_amdgcn_exp2f((m[tb] - mn) * kLog2e) + ((p0 + p1) + (p2 + p3));
+    m[tb] = mn;
   }
 }
 
-// ---- 4-wave fast path: one wave per SIMD, 128 (vocab) x 128 (token) per wave, accumulators in AGPRs.
+// ---- 4-wave fast path: one wave per SIMD, 128 (vocab) x 128 (token) per wave as 8 x 8 blocks of
+// v_mfma_f32_16x16x32_bf16 (the more power-efficient bf16 shape on this part), accumulators in AGPRs.
 // The K-loop of a vocabulary tile is one hand-scheduled inline-asm statement (w4_loop.inc, generated):
 // every MFMA is followed by at most one LDS read or one direct-to-LDS copy, fragments are double-
 // buffered in fixed VGPRs, the LM-head ring runs two K-tiles ahead and the hidden ring one.
@@ -412,7 +400,7 @@ __global__ __launch_bounds__(256) void masked_logits_kernel_w4(const KernelParam
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wv = wave & 1;   // vocabulary half of the tile
   const int wt = wave >> 1;  // token half of the tile
-  const int l32 = lane & 31, lhalf = lane >> 5;
+  const int l16 = lane & 15, q = lane >> 4;   // MFMA 16x16x32: row/column lane%16, k group lane/16
 
   int total = *p.count;
   if (total > p.max_rows) total = p.max_rows;
@@ -438,11 +426,11 @@ __global__ __launch_bounds__(256) void masked_logits_kernel_w4(const KernelParam
   const int nk = p.d / kTileK;
   const uint32_t w_row_bytes = (uint32_t)p.d * 2u;
 
-  // LDS read offsets per K sub-step: row (lane%32) of this wave's first 32-row block, swizzled chunk.
-  uint32_t rdw[4], rdh[4], woff[8];
+  // LDS read offsets per half K-tile: row (lane%16) of this wave's first 16-row block, swizzled chunk.
+  uint32_t rdw[2], rdh[2], woff[8];
 #pragma unroll
-  for (int ks = 0; ks < 4; ++ks) {
-    const uint32_t o = (uint32_t)(l32 * kRowBytes + (((2 * ks + lhalf) ^ ((l32 >> kSwzShift) & 7)) * 16));
+  for (int ks = 0; ks < 2; ++ks) {
+    const uint32_t o = (uint32_t)(l16 * kRowBytes + (((4 * ks + q) ^ ((l16 >> kSwzShift) & 7)) * 16));
     rdw[ks] = o + (uint32_t)(wv * 128 * kRowBytes);
     rdh[ks] = o + (uint32_t)(NW * kOperandBytes + wt * 128 * kRowBytes);
   }
@@ -515,18 +503,19 @@ __global__ __launch_bounds__(256) void masked_logits_kernel_w4(const KernelParam
     uint32_t st_wk = (uint32_t)(gw % nk), st_hk = (uint32_t)(gh % nk);
     uint32_t st_g = 0;
 
-    float run_m[4] = {kNeg, kNeg, kNeg, kNeg};
-    float run_s[4] = {0.f, 0.f, 0.f, 0.f};
-    int run_i[4] = {INT_MAX, INT_MAX, INT_MAX, INT_MAX};
+    float run_m[8], run_s[8];
+    int run_i[8];
+#pragma unroll
+    for (int tb = 0; tb < 8; ++tb) { run_m[tb] = kNeg; run_s[tb] = 0.f; run_i[tb] = INT_MAX; }
 
     for (int n = 0; n < ntile; ++n) {
-      f32x16 acc[4][4];
+      f32x4 acc[8][8];
 #pragma unroll
-      for (int bi = 0; bi < 4; ++bi)
+      for (int bi = 0; bi < 8; ++bi)
 #pragma unroll
-        for (int bj = 0; bj < 4; ++bj)
+        for (int bj = 0; bj < 8; ++bj)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) acc[bi][bj][r] = 0.f;
+          for (int r = 0; r < 4; ++r) acc[bi][bj][r] = 0.f;
       st_wsrc_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)st_wsrc_lo);
       st_wsrc_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)st_wsrc_hi);
       st_hsrc_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)st_hsrc_lo);
@@ -546,37 +535,42 @@ __global__ __launch_bounds__(256) void masked_logits_kernel_w4(const KernelParam
 #include "mosaic_w4_loop.inc"
       }
       const int v_tile0 = (vt0 + n) * kTileVocab;
-      const int vb = v_tile0 + wv * 128 + 4 * lhalf;
-      reduce_tile4<false>(acc, run_m, run_s, run_i, vb, p.V);
+      const int vb = v_tile0 + wv * 128 + 4 * q;
+      reduce_tile16(acc, run_m, run_s, run_i, vb);
     }
 
+    // Unit end: fold the four lanes that share a token (lane ^ 16, lane ^ 32), then the two waves that
+    // share it (vocabulary halves) through LDS, and publish one partial triple per row.
 #pragma unroll
-    for (int bj = 0; bj < 4; ++bj) {
-      const float m2 = __shfl_xor(run_m[bj], 32, 64);
-      const float s2 = __shfl_xor(run_s[bj], 32, 64);
-      const int i2 = __shfl_xor(run_i[bj], 32, 64);
-      merge_triple(run_m[bj], run_s[bj], run_i[bj], m2, s2, i2);
+    for (int tb = 0; tb < 8; ++tb) {
+#pragma unroll
+      for (int x = 16; x <= 32; x <<= 1) {
+        const float m2 = __shfl_xor(run_m[tb], x, 64);
+        const float s2 = __shfl_xor(run_s[tb], x, 64);
+        const int i2 = __shfl_xor(run_i[tb], x, 64);
+        merge_triple(run_m[tb], run_s[tb], run_i[tb], m2, s2, i2);
+      }
     }
     __syncthreads();  // every wave is done with the ring (the merge scratch aliases it)
-    if (wv == 1 && lhalf == 0) {
+    if (wv == 1 && q == 0) {
 #pragma unroll
-      for (int bj = 0; bj < 4; ++bj) {
-        const int e = (wt * 4 + bj) * 32 + l32;
-        red_m[e] = run_m[bj];
-        red_s[e] = run_s[bj];
-        red_i[e] = run_i[bj];
+      for (int tb = 0; tb < 8; ++tb) {
+        const int e = wt * 128 + tb * 16 + l16;
+        red_m[e] = run_m[tb];
+        red_s[e] = run_s[tb];
+        red_i[e] = run_i[tb];
       }
     }
     __syncthreads();
-    if (wv == 0 && lhalf == 0) {
+    if (wv == 0 && q == 0) {
 #pragma unroll
-      for (int bj = 0; bj < 4; ++bj) {
-        const int e = (wt * 4 + bj) * 32 + l32;
-        merge_triple(run_m[bj], run_s[bj], run_i[bj], red_m[e], red_s[e], red_i[e]);
+      for (int tb = 0; tb < 8; ++tb) {
+        const int e = wt * 128 + tb * 16 + l16;
+        merge_triple(run_m[tb], run_s[tb], run_i[tb], red_m[e], red_s[e], red_i[e]);
         const int64_t slot = (int64_t)sp * p.c_pad + tt * kTileRows + e;
-        p.part_m[slot] = run_m[bj];
-        p.part_s[slot] = run_s[bj];
-        p.part_i[slot] = run_i[bj];
+        p.part_m[slot] = run_m[tb];
+        p.part_s[slot] = run_s[tb];
+        p.part_i[slot] = run_i[tb];
       }
     }
     __syncthreads();

@@ -212,9 +212,10 @@ def test_chunking_is_a_bitwise_noop_and_deterministic():
             assert np.array_equal(base[k][:M], out[k][:M]), (K, k)
 
 
-def test_fast_and_general_kernels_agree_bitwise():
-    """Where both kernels apply they run the same MFMA sequence per logit and the same reduction order,
-    so their outputs must be identical, ragged last row tile included."""
+def test_fast_and_general_kernels_agree():
+    """The 4-wave kernel (16x16x32 MFMAs) and the general kernel (32x32x16) sum the same products in a
+    different association, so they agree to fp32 rounding, ragged last row tile included; each is checked
+    against the oracle on its own elsewhere."""
     print("fast vs general kernel", flush=True)
     for (T, d, V, p) in [(1300, 256, 2048, 0.8), (257, 64, 256, 1.0), (600, 448, 1024, 0.33)]:
         wl = workloads.small_random(T, d, V, p=p, seed=T, device=DEV)
@@ -224,8 +225,14 @@ def test_fast_and_general_kernels_agree_bitwise():
             plan.flags = binding.PLAN_GENERAL_KERNEL
         gen = run_hip(wl.hidden, wl.w, wl.mask, plan_edit=general)
         assert gen["op"].plan.flags == 1 and fast["op"].plan.flags == 0
-        for k in ("tok", "conf", "lse"):
-            assert np.array_equal(fast[k], gen[k]), (T, d, V, k)
+        M = fast["M"]
+        assert M == gen["M"]
+        want = oracle.positions(workloads.bf16_bits(wl.hidden), workloads.bf16_bits(wl.w), fast["idx"][:M])
+        clear = want.gap > 1e-4
+        assert np.array_equal(fast["tok"][:M][clear], gen["tok"][:M][clear])
+        assert np.allclose(fast["lse"][:M], gen["lse"][:M], atol=2e-5, rtol=0)
+        assert np.allclose(fast["conf"][:M], gen["conf"][:M], rtol=1e-4, atol=0)
+        assert np.array_equal(fast["tok"][M:], gen["tok"][M:])          # untouched tails
 
 
 def test_budget_forces_chunks_and_bounds_workspace():
