@@ -47,6 +47,10 @@ def _load():
         lib.oracle_positions.argtypes = [p, i64, i32, i64, p, i32, p, i64, p, p, p, p, p, p]
         lib.oracle_full_then_select.restype = i64
         lib.oracle_full_then_select.argtypes = [p, i64, i32, i64, p, i32, p, p, p, p, p, p, p]
+        lib.oracle_unmask_topn.restype = i64
+        lib.oracle_unmask_topn.argtypes = [p, p, p, i64, p, i32, p, p, p]
+        lib.oracle_shift_indices.restype = None
+        lib.oracle_shift_indices.argtypes = [p, i64, p, i32, p]
         lib.oracle_num_threads.restype = ctypes.c_int
         lib.oracle_num_threads.argtypes = []
         _lib = lib
@@ -141,3 +145,28 @@ def full_then_select(H: np.ndarray, W: np.ndarray, mask: np.ndarray):
     out = RowResults(res.tok[:m].copy(), res.conf[:m].copy(), res.lse[:m].copy(), res.gap[:m].copy(),
                      res.rowmax[:m].copy())
     return idx[:m].copy(), out
+
+
+def unmask_topn(conf, tok, idx, seq_starts, n_per_seq, tokens, mask):
+    """Per sequence, the n highest-confidence masked rows (ties: lower position) get their token written
+    into `tokens` and their mask byte cleared.  Returns (tokens, mask, number unmasked); inputs are copied."""
+    conf = np.ascontiguousarray(conf, dtype=np.float32)
+    tok = np.ascontiguousarray(tok, dtype=np.int32)
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    seq_starts = np.ascontiguousarray(seq_starts, dtype=np.int32)
+    n_per_seq = np.ascontiguousarray(n_per_seq, dtype=np.int32)
+    tokens = np.array(tokens, dtype=np.int32, copy=True)
+    mask = np.array(mask, dtype=np.uint8, copy=True)
+    assert conf.size == tok.size == idx.size and seq_starts.size == n_per_seq.size + 1
+    n = _load().oracle_unmask_topn(_ptr(conf), _ptr(tok), _ptr(idx), conf.size, _ptr(seq_starts), n_per_seq.size,
+                                   _ptr(n_per_seq), _ptr(tokens), _ptr(mask))
+    return tokens, mask, int(n)
+
+
+def shift_indices(idx, seq_starts):
+    """Hidden rows to read for Dream-style shifted prediction: idx - 1, except at sequence starts."""
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    seq_starts = np.ascontiguousarray(seq_starts, dtype=np.int32)
+    out = np.empty(max(idx.size, 1), np.int32)
+    _load().oracle_shift_indices(_ptr(idx), idx.size, _ptr(seq_starts), seq_starts.size - 1, _ptr(out))
+    return out[:idx.size].copy()

@@ -161,3 +161,49 @@ int oracle_num_threads(void) { return omp_get_max_threads(); }
 #else
 int oracle_num_threads(void) { return 1; }
 #endif
+
+/* ---- Sampling tail of a denoising step (paper section 2.1: the sampled tokens replace a selected
+ * subset of the [MASK] positions).  The paper does not say which subset; the reading taken is the
+ * one diffusion LLMs use for greedy decoding: per sequence, the n masked positions with the highest
+ * confidence, ties going to the lower position.  Plain selection by repeated maximum, O(n*m).
+ *
+ * conf/tok/idx: the M per-row results in ascending position order.  seq_starts: B+1 ascending flat
+ * positions delimiting the sequences.  n_per_seq: how many positions to unmask in each sequence
+ * (all of them if it has fewer masked positions).  tokens (int32[T]) and mask (uint8[T]) are updated
+ * in place.  Returns the number of positions unmasked. */
+int64_t oracle_unmask_topn(const float *conf, const int32_t *tok, const int32_t *idx, int64_t M,
+                           const int32_t *seq_starts, int32_t B, const int32_t *n_per_seq,
+                           int32_t *tokens, uint8_t *mask) {
+  int64_t done = 0;
+  uint8_t *taken = (uint8_t *)calloc((size_t)(M > 0 ? M : 1), 1);
+  for (int32_t b = 0; b < B; ++b) {
+    for (int32_t k = 0; k < n_per_seq[b]; ++k) {
+      int64_t best = -1;
+      for (int64_t j = 0; j < M; ++j) {
+        if (taken[j] || idx[j] < seq_starts[b] || idx[j] >= seq_starts[b + 1]) continue;
+        if (best < 0 || conf[j] > conf[best]) best = j; /* strict: earlier (lower) position wins ties */
+      }
+      if (best < 0) break;
+      taken[best] = 1;
+      tokens[idx[best]] = tok[best];
+      mask[idx[best]] = 0;
+      done += 1;
+    }
+  }
+  free(taken);
+  return done;
+}
+
+/* Dream-style shifted gather (paper section 4.5, last paragraph: the logits shift and concatenation
+ * of Dream replaced by a token-level alternative; no detail is given).  Reading: the prediction for
+ * position p is made from the hidden state of position p-1, except at the first position of a
+ * sequence, which keeps its own.  gather[j] = idx[j] - 1 unless idx[j] is a sequence start. */
+void oracle_shift_indices(const int32_t *idx, int64_t M, const int32_t *seq_starts, int32_t B,
+                          int32_t *gather) {
+  for (int64_t j = 0; j < M; ++j) {
+    int is_start = 0;
+    for (int32_t b = 0; b < B; ++b)
+      if (idx[j] == seq_starts[b]) is_start = 1;
+    gather[j] = is_start ? idx[j] : idx[j] - 1;
+  }
+}

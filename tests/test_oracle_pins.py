@@ -234,3 +234,42 @@ def test_statistics_of_gaussian_logits():
     r = oracle.positions(workloads.bf16_bits(wl.hidden), workloads.bf16_bits(wl.w), np.arange(0, 512, 8))
     assert abs(float(r.lse.mean()) - (math.log(8192) + 0.5)) < 0.15
     assert 3.2 < float(r.rowmax.mean()) < 4.6
+
+
+# ---------------------------------------------------------------- sampling tail (next row of the path)
+def test_unmask_topn_against_sorting_and_invariants():
+    """Pin: a stable sort by (-confidence, position) per sequence is the same selection; the rest of the
+    state must be untouched; duplicates of the confidence exercise the tie rule."""
+    rng = np.random.default_rng(4)
+    T, B = 300, 3
+    seq_starts = np.array([0, 100, 180, 300], np.int32)
+    mask = (rng.random(T) < 0.4).astype(np.uint8)
+    idx = np.nonzero(mask)[0].astype(np.int32)
+    conf = rng.choice(np.array([0.1, 0.25, 0.5, 0.75, 0.9], np.float32), idx.size)     # many ties
+    tok = rng.integers(0, 1000, idx.size).astype(np.int32)
+    tokens = np.full(T, -1, np.int32)
+    n_per_seq = np.array([5, 0, 1000], np.int32)                                        # some, none, all
+    new_tokens, new_mask, n = oracle.unmask_topn(conf, tok, idx, seq_starts, n_per_seq, tokens, mask)
+    want_tokens, want_mask, total = tokens.copy(), mask.copy(), 0
+    for b in range(B):
+        rows = [j for j in range(idx.size) if seq_starts[b] <= idx[j] < seq_starts[b + 1]]
+        rows.sort(key=lambda j: (-float(conf[j]), int(idx[j])))
+        for j in rows[:n_per_seq[b]]:
+            want_tokens[idx[j]] = tok[j]
+            want_mask[idx[j]] = 0
+            total += 1
+    assert n == total and np.array_equal(new_tokens, want_tokens) and np.array_equal(new_mask, want_mask)
+    assert np.array_equal(new_mask[100:180], mask[100:180])            # n = 0: sequence untouched
+    assert new_mask[180:].sum() == 0                                   # n >= m: everything unmasked
+    assert np.array_equal(tokens, np.full(T, -1, np.int32))            # inputs were not modified
+    # hand case: confidences 0.5 at positions 2 and 7, 0.9 at 5 -> n = 2 takes 5 then 2 (lower position on the tie)
+    t, m, _ = oracle.unmask_topn([0.5, 0.9, 0.5], [11, 22, 33], [2, 5, 7], [0, 10], [2], np.zeros(10, np.int32),
+                                 np.array([0, 0, 1, 0, 0, 1, 0, 1, 0, 0], np.uint8))
+    assert t.tolist() == [0, 0, 11, 0, 0, 22, 0, 0, 0, 0] and m.tolist() == [0, 0, 0, 0, 0, 0, 0, 1, 0, 0]
+
+
+def test_shift_indices_definition():
+    idx = np.array([0, 1, 5, 9, 10, 11, 19], np.int32)
+    got = oracle.shift_indices(idx, np.array([0, 10, 20], np.int32))
+    assert got.tolist() == [0, 0, 4, 8, 10, 10, 18]                   # sequence starts 0 and 10 keep their own row
+    assert oracle.shift_indices(np.array([], np.int32), np.array([0, 4], np.int32)).size == 0
