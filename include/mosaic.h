@@ -135,6 +135,36 @@ int mosaic_masked_logits_reduce(const void *hidden, int64_t T, int32_t d, int64_
                                 float *out_conf, float *out_lse, const mosaic_plan *plan, void *workspace,
                                 int64_t workspace_bytes, void *stream);
 
+/*
+ * Sampling tail of a denoising step (paper section 2.1: the tokens sampled from the logits replace a
+ * selected subset of the [MASK] positions; the paper does not say which subset -- the reading here is
+ * greedy decoding's: per sequence the n masked positions with the highest confidence, ties going to the
+ * lower position).  For every selected row j: tokens[idx[j]] = token[j] and mask[idx[j]] = 0; nothing
+ * else is written, so the next step's mosaic_mask_compact sees the updated mask.
+ *   conf, token, idx, count   dev, as produced by the two calls above (confidences are >= 0)
+ *   max_rows                  bound on *count
+ *   seq_starts                dev int32[num_seqs + 1], ascending flat positions delimiting the sequences
+ *                             (seq_starts[0] = 0, seq_starts[num_seqs] = T)
+ *   n_per_seq                 dev int32[num_seqs]; a sequence with fewer masked rows unmasks them all
+ *   tokens                    dev int32[T], the token sequence(s); mask: dev uint8[T]
+ * One workgroup per sequence; selection is exact (radix select on the fp32 bit patterns).
+ * Errors: INVALID_ARG (null pointer, negative size, num_seqs < 1), UNSUPPORTED_SHAPE (T or max_rows >= 2^31).
+ */
+int mosaic_unmask_topn(const float *conf, const int32_t *token, const int32_t *idx, const int32_t *count,
+                       int64_t max_rows, const int32_t *seq_starts, int32_t num_seqs, const int32_t *n_per_seq,
+                       int32_t *tokens, uint8_t *mask, int64_t T, void *stream);
+
+/*
+ * Dream-style shifted prediction without a shifted tensor (paper section 4.5, last paragraph: Dream's
+ * logits shift and concatenation replaced by a token-level alternative; no detail is given).  Reading:
+ * the prediction for position p comes from the hidden state of position p - 1, except at the first
+ * position of a sequence, which keeps its own.  out_gather[j] = that hidden row for idx[j]; pass it as
+ * `idx` to mosaic_masked_logits_reduce (outputs stay in the order of the masked positions).
+ *   idx, count, max_rows, seq_starts, num_seqs   as above;  out_gather: dev int32[max_rows]
+ */
+int mosaic_shift_indices(const int32_t *idx, const int32_t *count, int64_t max_rows, const int32_t *seq_starts,
+                         int32_t num_seqs, int32_t *out_gather, void *stream);
+
 /* Library version, "major.minor" as major*1000 + minor. */
 int mosaic_version(void);
 

@@ -27,7 +27,7 @@ PLAN_GENERAL_KERNEL = 1   # plan.flags bit: force the general 8-wave kernel
 
 EXPORTS = (
     "mosaic_status_string", "mosaic_plan_workspace", "mosaic_compact_scratch_bytes", "mosaic_mask_compact",
-    "mosaic_masked_logits_reduce", "mosaic_version",
+    "mosaic_masked_logits_reduce", "mosaic_unmask_topn", "mosaic_shift_indices", "mosaic_version",
 )
 
 
@@ -79,6 +79,10 @@ def lib():
         L.mosaic_masked_logits_reduce.restype = ctypes.c_int
         L.mosaic_masked_logits_reduce.argtypes = [p, i64, i32, i64, p, i32, p, p, i64, p, p, p,
                                                   ctypes.POINTER(MosaicPlan), p, i64, p]
+        L.mosaic_unmask_topn.restype = ctypes.c_int
+        L.mosaic_unmask_topn.argtypes = [p, p, p, p, i64, p, i32, p, p, p, i64, p]
+        L.mosaic_shift_indices.restype = ctypes.c_int
+        L.mosaic_shift_indices.argtypes = [p, p, i64, p, i32, p, p]
         _lib = L
     return _lib
 
@@ -148,6 +152,23 @@ def mosaic_masked_logits_reduce(hidden, w, idx, count, max_rows, out_token, out_
         _dev_ptr(out_lse, "out_lse", torch.float32), ctypes.byref(plan), _dev_ptr(workspace, "workspace"),
         workspace.numel() * workspace.element_size() if workspace is not None else 0, _stream_ptr(stream)),
         "mosaic_masked_logits_reduce")
+
+
+def mosaic_unmask_topn(conf, token, idx, count, max_rows, seq_starts, n_per_seq, tokens, mask, stream=None):
+    """Per sequence, write the tokens of the n highest-confidence masked rows and clear their mask bytes."""
+    _check(lib().mosaic_unmask_topn(
+        _dev_ptr(conf, "conf", torch.float32), _dev_ptr(token, "token", torch.int32), _dev_ptr(idx, "idx", torch.int32),
+        _dev_ptr(count, "count", torch.int32), max_rows, _dev_ptr(seq_starts, "seq_starts", torch.int32),
+        n_per_seq.numel(), _dev_ptr(n_per_seq, "n_per_seq", torch.int32), _dev_ptr(tokens, "tokens", torch.int32),
+        _dev_ptr(mask, "mask", torch.uint8), mask.numel(), _stream_ptr(stream)), "mosaic_unmask_topn")
+
+
+def mosaic_shift_indices(idx, count, max_rows, seq_starts, out_gather, stream=None):
+    """out_gather[j] = idx[j] - 1, except at the first position of a sequence (device tensors)."""
+    _check(lib().mosaic_shift_indices(
+        _dev_ptr(idx, "idx", torch.int32), _dev_ptr(count, "count", torch.int32), max_rows,
+        _dev_ptr(seq_starts, "seq_starts", torch.int32), seq_starts.numel() - 1,
+        _dev_ptr(out_gather, "out_gather", torch.int32), _stream_ptr(stream)), "mosaic_shift_indices")
 
 
 class MaskOnlyLogits:

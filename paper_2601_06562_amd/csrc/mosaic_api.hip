@@ -79,4 +79,30 @@ int mosaic_masked_logits_reduce(const void* hidden, int64_t T, int32_t d, int64_
   return rc == 0 ? MOSAIC_OK : MOSAIC_ERR_HIP;
 }
 
+int mosaic_unmask_topn(const float* conf, const int32_t* token, const int32_t* idx, const int32_t* count,
+                       int64_t max_rows, const int32_t* seq_starts, int32_t num_seqs, const int32_t* n_per_seq,
+                       int32_t* tokens, uint8_t* mask, int64_t T, void* stream) {
+  if (T < 0 || max_rows < 0 || max_rows > T || num_seqs < 1 || count == nullptr || seq_starts == nullptr ||
+      n_per_seq == nullptr)
+    return MOSAIC_ERR_INVALID_ARG;
+  if (T >= (int64_t)1 << 31) return MOSAIC_ERR_UNSUPPORTED_SHAPE;
+  if (max_rows == 0) return MOSAIC_OK;
+  if (conf == nullptr || token == nullptr || idx == nullptr || tokens == nullptr || mask == nullptr)
+    return MOSAIC_ERR_INVALID_ARG;
+  const int rc = mosaic::launch_unmask_topn(conf, token, idx, count, max_rows, seq_starts, num_seqs, n_per_seq, tokens,
+                                            mask, static_cast<hipStream_t>(stream));
+  return rc == 0 ? MOSAIC_OK : MOSAIC_ERR_HIP;
+}
+
+int mosaic_shift_indices(const int32_t* idx, const int32_t* count, int64_t max_rows, const int32_t* seq_starts,
+                         int32_t num_seqs, int32_t* out_gather, void* stream) {
+  if (max_rows < 0 || num_seqs < 1 || count == nullptr || seq_starts == nullptr) return MOSAIC_ERR_INVALID_ARG;
+  if (max_rows >= (int64_t)1 << 31) return MOSAIC_ERR_UNSUPPORTED_SHAPE;
+  if (max_rows == 0) return MOSAIC_OK;
+  if (idx == nullptr || out_gather == nullptr) return MOSAIC_ERR_INVALID_ARG;
+  const int rc = mosaic::launch_shift_indices(idx, count, max_rows, seq_starts, num_seqs, out_gather,
+                                              static_cast<hipStream_t>(stream));
+  return rc == 0 ? MOSAIC_OK : MOSAIC_ERR_HIP;
+}
+
 }  // extern "C"

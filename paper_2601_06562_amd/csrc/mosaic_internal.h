@@ -32,6 +32,13 @@ struct LogitsArgs {
 };
 int launch_masked_logits(const LogitsArgs& a, const mosaic_plan& plan, hipStream_t stream);
 
+// ---- sampling tail and shifted gather (mosaic_unmask.hip)
+int launch_unmask_topn(const float* conf, const int32_t* token, const int32_t* idx, const int32_t* count,
+                       int64_t max_rows, const int32_t* seq_starts, int32_t num_seqs, const int32_t* n_per_seq,
+                       int32_t* tokens, uint8_t* mask, hipStream_t stream);
+int launch_shift_indices(const int32_t* idx, const int32_t* count, int64_t max_rows, const int32_t* seq_starts,
+                         int32_t num_seqs, int32_t* gather, hipStream_t stream);
+
 // ---- host-side selector (mosaic_plan.cpp)
 int32_t choose_vocab_splits(int64_t row_tiles, int64_t vocab_tiles, int32_t num_cus);
 int64_t partials_bytes(int64_t rows_padded, int32_t splits);

@@ -118,3 +118,26 @@ def test_entry_points_validate_before_launch():
     assert call(plan=ctypes.byref(bad)) == binding.MOSAIC_ERR_INVALID_ARG
     small = binding.mosaic_plan_workspace(4096, 256, 4096, 126464, 0)                       # plan for fewer rows
     assert call(plan=ctypes.byref(small), ws_bytes=1 << 30) == binding.MOSAIC_ERR_INVALID_ARG
+
+
+def test_sampling_tail_entry_points_validate_before_launch():
+    L = binding.lib()
+    null, fake = ctypes.c_void_p(0), ctypes.c_void_p(0x1000)
+    un = lambda **kw: L.mosaic_unmask_topn(kw.get("conf", fake), fake, fake, kw.get("count", fake),
+                                           kw.get("max_rows", 100), kw.get("seq", fake), kw.get("B", 2), fake,
+                                           kw.get("tokens", fake), fake, kw.get("T", 1000), null)
+    assert un(count=null) == binding.MOSAIC_ERR_INVALID_ARG
+    assert un(seq=null) == binding.MOSAIC_ERR_INVALID_ARG
+    assert un(B=0) == binding.MOSAIC_ERR_INVALID_ARG
+    assert un(max_rows=2000) == binding.MOSAIC_ERR_INVALID_ARG            # > T
+    assert un(T=2 ** 31, max_rows=5) == binding.MOSAIC_ERR_UNSUPPORTED_SHAPE
+    assert un(conf=null) == binding.MOSAIC_ERR_INVALID_ARG
+    assert un(tokens=null) == binding.MOSAIC_ERR_INVALID_ARG
+    assert un(max_rows=0, conf=null) == binding.MOSAIC_OK                 # nothing to do
+    sh = lambda **kw: L.mosaic_shift_indices(kw.get("idx", fake), kw.get("count", fake), kw.get("max_rows", 10),
+                                             kw.get("seq", fake), kw.get("B", 1), kw.get("out", fake), null)
+    assert sh(count=null) == binding.MOSAIC_ERR_INVALID_ARG
+    assert sh(B=0) == binding.MOSAIC_ERR_INVALID_ARG
+    assert sh(out=null) == binding.MOSAIC_ERR_INVALID_ARG
+    assert sh(max_rows=-1) == binding.MOSAIC_ERR_INVALID_ARG
+    assert sh(max_rows=0, idx=null) == binding.MOSAIC_OK
