@@ -4,7 +4,9 @@
 One statement = the nk K-tiles of one vocabulary tile.  Per K-tile (step g) a wave issues 128
 v_mfma_f32_16x16x32_bf16 in two groups of 64 (k 0..31 and k 32..63 of the tile); after every second MFMA
 of a group's first half sits one of the 16 ds_read_b128 that fetch the next group's fragments, then one of
-up to 8 direct-to-LDS copies, so that nothing but MFMAs is ever waited on in steady state.
+up to 8 direct-to-LDS copies, so that nothing but MFMAs is ever waited on in steady state.  The steady-state body (1 <= g, g + 2 < total)
+contains no branch at all -- a taken branch costs more than one 16-cycle MFMA -- and all slot / pointer
+book-keeping is s_cselect arithmetic; the first step and the last two run a guarded copy of the same schedule.
 """
 import sys
 
@@ -13,6 +15,7 @@ FB = [[f"v[{148 + 64 * b + 4 * j}:{151 + 64 * b + 4 * j}]" for j in range(8)] fo
 VT0, VT1 = "v244", "v245"
 WSRC, HSRC = "s[96:97]", "s[98:99]"
 KT = "s95"
+NK128 = "s94"
 
 lines = []
 uid = [0]
@@ -56,39 +59,37 @@ def dma_h(i):
 
 
 def advance_h():
-    wrap, done = label("hwrap"), label("hdone")
+    """next hidden copy: k index, source pointer (forward 128 bytes, back nk*128 after the last K-tile), slot"""
     e("s_add_u32 %[hk], %[hk], 1")
-    e("s_cmp_eq_u32 %[hk], %[nk]")
-    e(f"s_cbranch_scc1 {wrap}")
     e("s_add_u32 s98, s98, 128")
     e("s_addc_u32 s99, s99, 0")
-    e(f"s_branch {done}")
-    e(f"{wrap}:")
-    e("s_mov_b32 %[hk], 0")
-    e("s_sub_u32 s98, s98, %[hwrap]")
+    e("s_cmp_eq_u32 %[hk], %[nk]")
+    e(f"s_cselect_b32 vcc_lo, {NK128}, 0")
+    e("s_cselect_b32 %[hk], 0, %[hk]")
+    e("s_sub_u32 s98, s98, vcc_lo")
     e("s_subb_u32 s99, s99, 0")
-    e(f"{done}:")
     e("s_xor_b32 %[hdst], %[hdst], 0x8000")
 
 
 def advance_w():
-    wrap, done, nowrap = label("wwrap"), label("wdone"), label("wslot")
+    """next LM-head copy: k index, source pointer (forward 128 bytes or on to the next 256 rows), slot"""
     e("s_add_u32 %[wk], %[wk], 1")
     e("s_cmp_eq_u32 %[wk], %[nk]")
-    e(f"s_cbranch_scc1 {wrap}")
-    e("s_add_u32 s96, s96, 128")
+    e("s_cselect_b32 vcc_lo, %[wwrap], 128")
+    e("s_cselect_b32 %[wk], 0, %[wk]")
+    e("s_add_u32 s96, s96, vcc_lo")
     e("s_addc_u32 s97, s97, 0")
-    e(f"s_branch {done}")
-    e(f"{wrap}:")
-    e("s_mov_b32 %[wk], 0")
-    e("s_add_u32 s96, s96, %[wwrap]")
-    e("s_addc_u32 s97, s97, 0")
-    e(f"{done}:")
     e("s_add_u32 %[wdst], %[wdst], 0x8000")
     e("s_cmp_ge_u32 %[wdst], 0x18000")
-    e(f"s_cbranch_scc0 {nowrap}")
-    e("s_sub_u32 %[wdst], %[wdst], 0x18000")
-    e(f"{nowrap}:")
+    e("s_cselect_b32 vcc_lo, 0x18000, 0")
+    e("s_sub_u32 %[wdst], %[wdst], vcc_lo")
+
+
+def rotate_read_slots():
+    e("s_add_u32 %[wrd], %[wrd], 0x8000")
+    e("s_cmp_ge_u32 %[wrd], 0x18000")
+    e("s_cselect_b32 %[wrd], 0, %[wrd]")
+    e("s_xor_b32 %[hrd], %[hrd], 0x8000")
 
 
 def cond_g_ge1_and(plus):
@@ -117,7 +118,15 @@ def group(buf, rd=None, dma=None, cond=None, after=None):
         mfma(*order[k], buf)
         if rd and k % 2 == 0:
             e(rd[k // 2])
-    if dma:
+    if dma and cond is None:
+        for k in range(32, 48):
+            mfma(*order[k], buf)
+            if k % 2 == 0:
+                for x in dma[(k - 32) // 2]:
+                    e(x)
+        if after:
+            after()
+    elif dma:
         skip, join = label("nodma"), label("join")
         cond()
         e(f"s_cbranch_scc0 {skip}")
@@ -140,56 +149,59 @@ def group(buf, rd=None, dma=None, cond=None, after=None):
         mfma(*order[k], buf)
 
 
+def step_end(top):
+    e("s_add_u32 %[g], %[g], 1")
+    e(f"s_add_u32 {KT}, {KT}, 1")
+    e(f"s_cmp_lt_u32 {KT}, %[nk]")
+    e(f"s_cbranch_scc1 {top}")
+
+
 def build():
     # entry: pointers into fixed SGPR pairs, first fragments of the current step
     e("s_mov_b32 s96, %[wsrc_lo]")
     e("s_mov_b32 s97, %[wsrc_hi]")
     e("s_mov_b32 s98, %[hsrc_lo]")
     e("s_mov_b32 s99, %[hsrc_hi]")
+    e(f"s_add_u32 {NK128}, %[hwrap], 128")      # nk * 128
     e(f"s_mov_b32 {KT}, 0")
     read_addr(0)
     for r in reads(0):
         e(r)
     e("s_nop 7")
-    step = label("step")
-    e(f"{step}:")
-    # first half (k 0..31): MFMAs on buffer 0, fragments of the second half -> buffer 1, the LM-head copies
-    # of tile g+2 (decided at the previous sync)
+    top, generic, out = label("top"), label("generic"), label("out")
+    e(f"{top}:")
+    # Steady state (1 <= g and g + 2 < total): every copy and the sync happen, no branch inside the body.
+    cond_g_ge1_and(2)
+    e(f"s_cbranch_scc0 {generic}")
+    read_addr(1)
+    group(0, rd=reads(1), dma=[dma_w(i) for i in range(8)], after=advance_w)     # LM-head tile g+2
+    e("s_waitcnt lgkmcnt(0)")
+    e("s_waitcnt vmcnt(8)")       # all but the LM-head tile just issued
+    e("s_barrier")
+    rotate_read_slots()
+    read_addr(0)
+    group(1, rd=reads(0), dma=[dma_h(i) for i in range(8)], after=advance_h)     # hidden tile g+2
+    step_end(top)
+    e(f"s_branch {out}")
+    # First step and the last two: same schedule with every part guarded.
+    e(f"{generic}:")
     read_addr(1)
     group(0, rd=reads(1), dma=[dma_w(i) for i in range(8)], cond=lambda: cond_g_ge1_and(2), after=advance_w)
-    # sync (if a next step exists): every wave holds all fragments of step g in registers
     nosync, stepend = label("nosync"), label("stepend")
     cond_plus(1)
     e(f"s_cbranch_scc0 {nosync}")
     e("s_waitcnt lgkmcnt(0)")
-    w0, wd = label("wait0"), label("waited")
-    cond_g_ge1_and(2)
-    e(f"s_cbranch_scc0 {w0}")
-    e("s_waitcnt vmcnt(8)")
-    e(f"s_branch {wd}")
-    e(f"{w0}:")
-    e("s_waitcnt vmcnt(0)")
-    e(f"{wd}:")
+    e("s_waitcnt vmcnt(0)")       # outside the steady state no copy younger than step g+1 needs to stay in flight
     e("s_barrier")
-    nowrap = label("rdslot")
-    e("s_add_u32 %[wrd], %[wrd], 0x8000")
-    e("s_cmp_ge_u32 %[wrd], 0x18000")
-    e(f"s_cbranch_scc0 {nowrap}")
-    e("s_mov_b32 %[wrd], 0")
-    e(f"{nowrap}:")
-    e("s_xor_b32 %[hrd], %[hrd], 0x8000")
-    # second half (k 32..63): buffer 1, fragments of the next step's first half -> buffer 0 (new slots),
-    # the hidden copies of tile g+2
+    rotate_read_slots()
     read_addr(0)
     group(1, rd=reads(0), dma=[dma_h(i) for i in range(8)], cond=lambda: cond_plus(2), after=advance_h)
     e(f"s_branch {stepend}")
     e(f"{nosync}:")
     group(1)
     e(f"{stepend}:")
-    e("s_add_u32 %[g], %[g], 1")
-    e(f"s_add_u32 {KT}, {KT}, 1")
-    e(f"s_cmp_lt_u32 {KT}, %[nk]")
-    e(f"s_cbranch_scc1 {step}")
+    step_end(top)
+    e(f"{out}:")
     # exit: results visible to the VALU, pointers back to the operands
     e("s_nop 15")
     e("s_nop 15")
@@ -215,7 +227,7 @@ def main(path):
         ins.append(f'[hoff{i}] "v"(hoff[{i}])')
     for name in ("total", "nk", "wwrap", "hwrap"):
         ins.append(f'[{name}] "s"(st_{name})')
-    clob = [f'"v{r}"' for r in range(116, 246)] + ['"s95"', '"s96"', '"s97"', '"s98"', '"s99"', '"vcc"', '"scc"', '"m0"',
+    clob = [f'"v{r}"' for r in range(116, 246)] + ['"s94"', '"s95"', '"s96"', '"s97"', '"s98"', '"s99"', '"vcc"', '"scc"', '"m0"',
                                                      '"memory"']
     with open(path, "w") as f:
         f.write("// GENERATED by gen_w4_loop.py -- do not edit.  The K-loop of one vocabulary tile (4-wave kernel).\n")
