@@ -10,9 +10,11 @@ book-keeping is s_cselect arithmetic; the first step and the last two run a guar
 """
 import sys
 
-FA = [[f"v[{116 + 64 * b + 4 * i}:{119 + 64 * b + 4 * i}]" for i in range(8)] for b in range(2)]
-FB = [[f"v[{148 + 64 * b + 4 * j}:{151 + 64 * b + 4 * j}]" for j in range(8)] for b in range(2)]
-VT0, VT1 = "v244", "v245"
+# fragment double buffer (2 x 16 tuples of 4 VGPRs) and two address temporaries: early-clobber outputs, so the
+# register allocator places them (a fixed clobbered range made it spill everything that lives across the loop)
+FA = [[f"%[fa{b}{i}]" for i in range(8)] for b in range(2)]
+FB = [[f"%[fb{b}{j}]" for j in range(8)] for b in range(2)]
+VT0, VT1 = "%[vt0]", "%[vt1]"
 WSRC, HSRC = "s[96:97]", "s[98:99]"
 KT = "s95"
 NK128 = "s94"
@@ -216,6 +218,13 @@ def main(path):
     outs = [f'[a{bi}{bj}] "+a"(acc[{bi}][{bj}])' for bi in range(8) for bj in range(8)]
     for name in ("wsrc_lo", "wsrc_hi", "hsrc_lo", "hsrc_hi", "wrd", "hrd", "wdst", "hdst", "wk", "hk", "g"):
         outs.append(f'[{name}] "+s"(st_{name})')
+    for b in range(2):
+        for i in range(8):
+            outs.append(f'[fa{b}{i}] "=&v"(frag_a[{b}][{i}])')
+        for j in range(8):
+            outs.append(f'[fb{b}{j}] "=&v"(frag_b[{b}][{j}])')
+    outs.append('[vt0] "=&v"(addr_tmp0)')
+    outs.append('[vt1] "=&v"(addr_tmp1)')
     ins = []
     for k in range(2):
         ins.append(f'[rdw{k}] "v"(rdw[{k}])')
@@ -227,7 +236,7 @@ def main(path):
         ins.append(f'[hoff{i}] "v"(hoff[{i}])')
     for name in ("total", "nk", "wwrap", "hwrap"):
         ins.append(f'[{name}] "s"(st_{name})')
-    clob = [f'"v{r}"' for r in range(116, 246)] + ['"s94"', '"s95"', '"s96"', '"s97"', '"s98"', '"s99"', '"vcc"', '"scc"', '"m0"',
+    clob = ['"s94"', '"s95"', '"s96"', '"s97"', '"s98"', '"s99"', '"vcc"', '"scc"', '"m0"',
                                                      '"memory"']
     with open(path, "w") as f:
         f.write("// GENERATED by gen_w4_loop.py -- do not edit.  The K-loop of one vocabulary tile (4-wave kernel).\n")

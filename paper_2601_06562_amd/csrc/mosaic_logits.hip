@@ -353,30 +353,32 @@ using f32x4 = __attribute__((ext_vector_type(4))) float;
 __device__ __forceinline__ void reduce_tile16(f32x4 (&acc)[8][8], float (&m)[8], float (&s)[8], int (&ix)[8], int vb) {
 #pragma unroll
   for (int tb = 0; tb < 8; ++tb) {
-    float mt = kNeg;
+    float x[32];   // this column's 32 logits, read out of the accumulators once
 #pragma unroll
     for (int bi = 0; bi < 8; ++bi)
 #pragma unroll
-      for (int r = 0; r < 4; ++r) mt = fmaxf(mt, acc[bi][tb][r]);
+      for (int r = 0; r < 4; ++r) x[bi * 4 + r] = acc[bi][tb][r];
+    float mt = kNeg;
+#pragma unroll
+    for (int e = 0; e < 32; ++e) mt = fmaxf(mt, x[e]);
     int sel = 0;
 #pragma unroll
-    for (int bi = 7; bi >= 0; --bi)
-#pragma unroll
-      for (int r = 3; r >= 0; --r) sel = (acc[bi][tb][r] == mt) ? (bi * 16 + r) : sel;  // descending: lowest id wins
+    for (int e = 31; e >= 0; --e) sel = (x[e] == mt) ? ((e >> 2) * 16 + (e & 3)) : sel;  // descending: lowest id wins
     const bool upd = mt > m[tb];
     ix[tb] = upd ? vb + sel : ix[tb];
     const float mn = fmaxf(m[tb], mt);
     const float nml = -mn * kLog2e;
     float p0 = 0.f, p1 = 0.f, p2 = 0.f, p3 = 0.f;
 #pragma unroll
-    for (int bi = 0; bi < 8; ++bi) {
-      p0 += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[bi][tb][0], kLog2e, nml));
-      p1 += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[bi][tb][1], kLog2e, nml));
-      p2 += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[bi][tb][2], kLog2e, nml));
-      p3 += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[bi][tb][3], kLog2e, nml));
+    for (int e = 0; e < 32; e += 4) {
+      p0 += __builtin_amdgcn_exp2f(__builtin_fmaf(x[e + 0], kLog2e, nml));
+      p1 += __builtin_amdgcn_exp2f(__builtin_fmaf(x[e + 1], kLog2e, nml));
+      p2 += __builtin_amdgcn_exp2f(__builtin_fmaf(x[e + 2], kLog2e, nml));
+      p3 += __builtin_amdgcn_exp2f(__builtin_fmaf(x[e + 3], kLog2e, nml));
     }
     s[tb] = s[tb] * __builtin_amdgcn_exp2f((m[tb] - mn) * kLog2e) + ((p0 + p1) + (p2 + p3));
     m[tb] = mn;
+    __builtin_amdgcn_sched_barrier(0);   // one column at a time: keeps the live set at ~40 registers
   }
 }
 
@@ -532,6 +534,8 @@ __global__ __launch_bounds__(256) void masked_logits_kernel_w4(const KernelParam
       const uint32_t st_nk = (uint32_t)__builtin_amdgcn_readfirstlane((int)u_nk);
       const uint32_t st_wwrap = (uint32_t)__builtin_amdgcn_readfirstlane((int)u_wwrap);
       const uint32_t st_hwrap = (uint32_t)__builtin_amdgcn_readfirstlane((int)u_hwrap);
+        bf16x8 frag_a[2][8], frag_b[2][8];   // written and consumed inside the loop only
+        uint32_t addr_tmp0, addr_tmp1;
 #include "mosaic_w4_loop.inc"
       }
       const int v_tile0 = (vt0 + n) * kTileVocab;
