@@ -51,6 +51,17 @@ def _load():
         lib.oracle_unmask_topn.argtypes = [p, p, p, i64, p, i32, p, p, p]
         lib.oracle_shift_indices.restype = None
         lib.oracle_shift_indices.argtypes = [p, i64, p, i32, p]
+        lib.oracle_philox4x32_10.restype = None
+        lib.oracle_philox4x32_10.argtypes = [p, p, p]
+        lib.oracle_uniform.restype = ctypes.c_double
+        lib.oracle_uniform.argtypes = [ctypes.c_uint64, i32, i32]
+        lib.oracle_gumbel.restype = ctypes.c_double
+        lib.oracle_gumbel.argtypes = [ctypes.c_uint64, i32, i32]
+        lib.oracle_row_sample.restype = None
+        lib.oracle_row_sample.argtypes = [p, i32, ctypes.c_double, ctypes.c_uint64, i32, p, p, p, p]
+        lib.oracle_positions_sample.restype = ctypes.c_int
+        lib.oracle_positions_sample.argtypes = [p, i64, i32, i64, p, i32, p, i64, ctypes.c_double, ctypes.c_uint64,
+                                                p, p, p, p]
         lib.oracle_num_threads.restype = ctypes.c_int
         lib.oracle_num_threads.argtypes = []
         _lib = lib
@@ -170,3 +181,45 @@ def shift_indices(idx, seq_starts):
     out = np.empty(max(idx.size, 1), np.int32)
     _load().oracle_shift_indices(_ptr(idx), idx.size, _ptr(seq_starts), seq_starts.size - 1, _ptr(out))
     return out[:idx.size].copy()
+
+
+def philox4x32_10(ctr, key):
+    ctr = np.ascontiguousarray(ctr, dtype=np.uint32)
+    key = np.ascontiguousarray(key, dtype=np.uint32)
+    out = np.empty(4, np.uint32)
+    _load().oracle_philox4x32_10(_ptr(ctr), _ptr(key), _ptr(out))
+    return out
+
+
+def uniform(seed, position, v) -> float:
+    return float(_load().oracle_uniform(seed, position, v))
+
+
+def gumbel(seed, position, v) -> float:
+    return float(_load().oracle_gumbel(seed, position, v))
+
+
+def row_sample(x, tau, seed, position):
+    """(tok, conf, lse, ygap) of one row of fp32 logits under Gumbel-max sampling with temperature tau."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    tok = ctypes.c_int32()
+    conf, lse, gap = ctypes.c_float(), ctypes.c_float(), ctypes.c_float()
+    _load().oracle_row_sample(_ptr(x), x.size, float(tau), int(seed), int(position), ctypes.byref(tok),
+                              ctypes.byref(conf), ctypes.byref(lse), ctypes.byref(gap))
+    return int(tok.value), float(conf.value), float(lse.value), float(gap.value)
+
+
+def positions_sample(H, W, pos, tau, seed):
+    """Sampled token, its probability, lse and the perturbed top-2 gap at the listed positions."""
+    H, W = _u16(H, "H"), _u16(W, "W")
+    T, d = H.shape
+    V, _ = W.shape
+    pos = np.ascontiguousarray(pos, dtype=np.int64)
+    n = pos.size
+    tok, conf = np.empty(n, np.int32), np.empty(n, np.float32)
+    lse, gap = np.empty(n, np.float32), np.empty(n, np.float32)
+    rc = _load().oracle_positions_sample(_ptr(H), T, d, d, _ptr(W), V, _ptr(pos), n, float(tau), int(seed),
+                                         _ptr(tok), _ptr(conf), _ptr(lse), _ptr(gap))
+    if rc != 0:
+        raise ValueError("position out of range")
+    return tok, conf, lse, gap

@@ -207,3 +207,77 @@ void oracle_shift_indices(const int32_t *idx, int64_t M, const int32_t *seq_star
     gather[j] = is_start ? idx[j] : idx[j] - 1;
   }
 }
+
+/* ---- Sampling with temperature (rest of the sampling tail; paper section 2.1 only says that tokens
+ * are sampled from the logits).  Reading: the Gumbel-max rule diffusion LLMs use, noise scaled by the
+ * temperature tau:   tok = argmax_v ( x[v] + tau * g[v] ),  g = -ln(-ln u),  u uniform in (0,1),
+ * conf = softmax(x)[tok] = exp(x[tok] - lse)  (the probability of the token actually picked),
+ * lse as before.  tau = 0 is the greedy rule.  The random numbers are a pure function of
+ * (seed, position, vocabulary id), so the HIP path can draw the same ones: Philox4x32-10 (Salmon et al.,
+ * "Parallel random numbers: as easy as 1, 2, 3", SC'11) with key = (seed low, seed high) and counter =
+ * (v / 4, position, 0, 0); output word v % 4; u = ((word >> 9) + 1/2) * 2^-23, which is exact in fp32
+ * as well (23 bits plus the half), never 0 and never 1. */
+static inline uint32_t mulhi32(uint32_t a, uint32_t b) { return (uint32_t)(((uint64_t)a * (uint64_t)b) >> 32); }
+
+void oracle_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]) {
+  uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3], k0 = key[0], k1 = key[1];
+  for (int round = 0; round < 10; ++round) {
+    if (round > 0) { k0 += 0x9E3779B9u; k1 += 0xBB67AE85u; }
+    uint32_t hi0 = mulhi32(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+    uint32_t hi1 = mulhi32(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+    uint32_t n0 = hi1 ^ c1 ^ k0, n1 = lo1, n2 = hi0 ^ c3 ^ k1, n3 = lo0;
+    c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+  }
+  out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* Uniform in (0,1) for (seed, position, vocabulary id); 23 bits, never 0 or 1. */
+double oracle_uniform(uint64_t seed, int32_t position, int32_t v) {
+  uint32_t ctr[4] = {(uint32_t)v >> 2, (uint32_t)position, 0u, 0u};
+  uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+  uint32_t out[4];
+  oracle_philox4x32_10(ctr, key, out);
+  return ((double)(out[v & 3] >> 9) + 0.5) * (1.0 / 8388608.0);
+}
+
+double oracle_gumbel(uint64_t seed, int32_t position, int32_t v) {
+  return -log(-log(oracle_uniform(seed, position, v)));
+}
+
+/* One row: logits x[V] (fp32) -> sampled token, its probability, lse, and the top-2 gap of the
+ * perturbed scores (for the acceptance rule). */
+void oracle_row_sample(const float *x, int32_t V, double tau, uint64_t seed, int32_t position,
+                       int32_t *tok, float *conf, float *lse, float *ygap) {
+  double m = (double)x[0];
+  for (int32_t v = 1; v < V; ++v) if ((double)x[v] > m) m = (double)x[v];
+  double s = 0.0;
+  for (int32_t v = 0; v < V; ++v) s += exp((double)x[v] - m);
+  double l = m + log(s);
+  double best = -INFINITY, second = -INFINITY;
+  int32_t arg = 0;
+  for (int32_t v = 0; v < V; ++v) {
+    double y = (double)x[v] + (tau > 0.0 ? tau * oracle_gumbel(seed, position, v) : 0.0);
+    if (y > best) { second = best; best = y; arg = v; }   /* strict: lowest id on ties */
+    else if (y > second) second = y;
+  }
+  *tok = arg;
+  *lse = (float)l;
+  *conf = (float)exp((double)x[arg] - l);
+  *ygap = (V > 1) ? (float)(best - second) : INFINITY;
+}
+
+/* Sampling at the listed positions (restriction of the full computation, as oracle_positions). */
+int oracle_positions_sample(const uint16_t *H, int64_t T, int32_t d, int64_t ld_h, const uint16_t *W, int32_t V,
+                            const int64_t *pos, int64_t n, double tau, uint64_t seed, int32_t *tok, float *conf,
+                            float *lse, float *ygap) {
+  for (int64_t j = 0; j < n; ++j)
+    if (pos[j] < 0 || pos[j] >= T) return -1;
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int64_t j = 0; j < n; ++j) {
+    float *x = (float *)malloc(sizeof(float) * (size_t)V);
+    oracle_row_logits(H + (size_t)pos[j] * (size_t)ld_h, W, d, V, x);
+    oracle_row_sample(x, V, tau, seed, (int32_t)pos[j], &tok[j], &conf[j], &lse[j], &ygap[j]);
+    free(x);
+  }
+  return 0;
+}
