@@ -28,6 +28,9 @@ def main():
     ap.add_argument("--budget-bytes", type=int, default=0, help="workspace budget for the chunk-size selector")
     ap.add_argument("--cpu-rows", type=int, default=4096, help="rows of the workload the CPU oracle is timed on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--temperature", type=float, default=0.0,
+                    help="> 0 times the Gumbel-max sampling variant of the fused kernel instead of the greedy one "
+                         "(not the headline configuration)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain 1 GiB device-to-device copy (for scaling rocprofv3's FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
@@ -53,15 +56,21 @@ def main():
         return
     wl = workloads.make(args.workload, device=dev)
     M = wl.M
-    op = MaskOnlyLogits(wl.T, wl.d, wl.V, max_rows=M, budget_bytes=args.budget_bytes, device=dev)
+    op = MaskOnlyLogits(wl.T, wl.d, wl.V, max_rows=M, budget_bytes=args.budget_bytes, device=dev,
+                        sampling=args.temperature > 0)
     stream = torch.cuda.current_stream()
 
     def step(ev=None):
         binding.mosaic_mask_compact(wl.mask, op.idx, op.count, op.scratch, stream)
         if ev is not None:
             ev[0].record(stream)
-        binding.mosaic_masked_logits_reduce(wl.hidden, wl.w, op.idx, op.count, op.max_rows, op.token, op.conf,
-                                            op.lse, op.plan, op.workspace, stream)
+        if args.temperature > 0:
+            binding.mosaic_masked_logits_sample(wl.hidden, wl.w, op.idx, op.count, op.max_rows, args.temperature,
+                                                20260106 + (0 if ev is None else id(ev) & 0xFFFF), op.token, op.conf,
+                                                op.lse, op.plan, op.workspace, stream)
+        else:
+            binding.mosaic_masked_logits_reduce(wl.hidden, wl.w, op.idx, op.count, op.max_rows, op.token, op.conf,
+                                                op.lse, op.plan, op.workspace, stream)
         if ev is not None:
             ev[1].record(stream)
 
@@ -101,7 +110,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": args.workload, "T": wl.T, "d": wl.d, "V": wl.V, "masked_rows": M,
                    "num_chunks": op.plan.num_chunks, "rows_per_chunk": op.plan.rows_per_chunk,
-                   "vocab_splits": op.plan.vocab_splits, "grid": op.plan.grid},
+                   "vocab_splits": op.plan.vocab_splits, "grid": op.plan.grid,
+                   "decode": "greedy" if args.temperature <= 0 else f"gumbel-max tau={args.temperature}"},
         "tflops": flop / sec_per_step / 1e12,
         "pct_bf16_mfma_peak": 100.0 * flop / sec_per_step / 1e12 / PEAK_BF16_TFLOPS,
         "peak_workspace_bytes": op.workspace_bytes,
@@ -112,7 +122,7 @@ def main():
                      "algorithmic_bytes": 2 * wl.V * wl.d + 2 * M * wl.d + 12 * M},
     }
 
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.temperature <= 0:
         import oracle
         rows = min(args.cpu_rows, M)
         rng = np.random.default_rng(0)

@@ -136,6 +136,31 @@ int mosaic_masked_logits_reduce(const void *hidden, int64_t T, int32_t d, int64_
                                 int64_t workspace_bytes, void *stream);
 
 /*
+ * The same fused pass with temperature sampling in place of the arg-max (paper section 2.1: tokens are
+ * sampled from the logits; the paper fixes no sampler -- the reading here is the Gumbel-max form of
+ * categorical sampling at temperature tau, which draws v with probability softmax(x / tau)[v] and needs
+ * no second pass over the logits).  For every j < *count, with t = idx[j] and x as above:
+ *   g[v]         = -ln(-ln u[v]),  u[v] = ((word >> 9) + 1/2) * 2^-23, where word is output word v % 4 of
+ *                  Philox4x32-10 (Salmon et al., SC'11) with key = (low, high 32 bits of seed) and
+ *                  counter = (v / 4, t, 0, 0): the noise depends on (seed, position, id) only, not on the
+ *                  chunking, the vocabulary split or the launch shape
+ *   out_token[j] = lowest v attaining max_v ( x[v] + temperature * g[v] )      (fp32)
+ *   out_lse[j]   = log sum_v exp(x[v])                                          (of the unperturbed logits)
+ *   out_conf[j]  = exp(x[out_token[j]] - out_lse[j])
+ * temperature == 0 is exactly mosaic_masked_logits_reduce.  All other arguments are as there, except
+ *   workspace  dev, >= mosaic_sample_workspace_bytes(plan) when temperature > 0 (20 bytes per row of a
+ *              chunk and vocabulary split instead of 12), 16-byte aligned
+ *   seed       any value; callers advance it per denoising step
+ * Additional errors: INVALID_ARG for a negative, NaN or infinite temperature.
+ * mosaic_sample_workspace_bytes returns 0 for a NULL or unfilled plan.
+ */
+int64_t mosaic_sample_workspace_bytes(const mosaic_plan *plan);
+int mosaic_masked_logits_sample(const void *hidden, int64_t T, int32_t d, int64_t ld_h, const void *w, int32_t V,
+                                const int32_t *idx, const int32_t *count, int64_t max_rows, float temperature,
+                                uint64_t seed, int32_t *out_token, float *out_conf, float *out_lse,
+                                const mosaic_plan *plan, void *workspace, int64_t workspace_bytes, void *stream);
+
+/*
  * Sampling tail of a denoising step (paper section 2.1: the tokens sampled from the logits replace a
  * selected subset of the [MASK] positions; the paper does not say which subset -- the reading here is
  * greedy decoding's: per sequence the n masked positions with the highest confidence, ties going to the

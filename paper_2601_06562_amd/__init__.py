@@ -5,5 +5,6 @@ tensors to it, ``workloads`` draws the seeded synthetic inputs, ``build`` compil
 """
 from . import binding, workloads  # noqa: F401
 from .binding import (MaskOnlyLogits, MosaicError, MosaicPlan, mosaic_compact_scratch_bytes,  # noqa: F401
-                      mosaic_mask_compact, mosaic_masked_logits_reduce, mosaic_plan_workspace,
+                      mosaic_mask_compact, mosaic_masked_logits_reduce, mosaic_masked_logits_sample,
+                      mosaic_plan_workspace, mosaic_sample_workspace_bytes,
                       mosaic_shift_indices, mosaic_unmask_topn)

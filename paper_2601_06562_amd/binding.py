@@ -27,7 +27,7 @@ PLAN_GENERAL_KERNEL = 1   # plan.flags bit: force the general 8-wave kernel
 
 EXPORTS = (
     "mosaic_status_string", "mosaic_plan_workspace", "mosaic_compact_scratch_bytes", "mosaic_mask_compact",
-    "mosaic_masked_logits_reduce", "mosaic_unmask_topn", "mosaic_shift_indices", "mosaic_version",
+    "mosaic_masked_logits_reduce", "mosaic_sample_workspace_bytes", "mosaic_masked_logits_sample", "mosaic_unmask_topn", "mosaic_shift_indices", "mosaic_version",
 )
 
 
@@ -79,6 +79,11 @@ def lib():
         L.mosaic_masked_logits_reduce.restype = ctypes.c_int
         L.mosaic_masked_logits_reduce.argtypes = [p, i64, i32, i64, p, i32, p, p, i64, p, p, p,
                                                   ctypes.POINTER(MosaicPlan), p, i64, p]
+        L.mosaic_sample_workspace_bytes.restype = i64
+        L.mosaic_sample_workspace_bytes.argtypes = [ctypes.POINTER(MosaicPlan)]
+        L.mosaic_masked_logits_sample.restype = ctypes.c_int
+        L.mosaic_masked_logits_sample.argtypes = [p, i64, i32, i64, p, i32, p, p, i64, ctypes.c_float, ctypes.c_uint64,
+                                                  p, p, p, ctypes.POINTER(MosaicPlan), p, i64, p]
         L.mosaic_unmask_topn.restype = ctypes.c_int
         L.mosaic_unmask_topn.argtypes = [p, p, p, p, i64, p, i32, p, p, p, i64, p]
         L.mosaic_shift_indices.restype = ctypes.c_int
@@ -154,6 +159,31 @@ def mosaic_masked_logits_reduce(hidden, w, idx, count, max_rows, out_token, out_
         "mosaic_masked_logits_reduce")
 
 
+def mosaic_sample_workspace_bytes(plan) -> int:
+    """Workspace bytes mosaic_masked_logits_sample needs for this plan at temperature > 0."""
+    return int(lib().mosaic_sample_workspace_bytes(ctypes.byref(plan)))
+
+
+def mosaic_masked_logits_sample(hidden, w, idx, count, max_rows, temperature, seed, out_token, out_conf, out_lse, plan,
+                                workspace, stream=None):
+    """As mosaic_masked_logits_reduce, with Gumbel-max sampling at `temperature` from the 64-bit `seed`."""
+    T, d = hidden.shape
+    V, d2 = w.shape
+    if d != d2:
+        raise ValueError("hidden and w disagree on d")
+    if hidden.stride(1) != 1 or not w.is_contiguous():
+        raise ValueError("hidden rows and w must be dense along d")
+    ld_h = hidden.stride(0) if T > 1 else d
+    _check(lib().mosaic_masked_logits_sample(
+        _dev_ptr(hidden, "hidden", torch.bfloat16), T, d, ld_h, _dev_ptr(w, "w", torch.bfloat16), V,
+        _dev_ptr(idx, "idx", torch.int32), _dev_ptr(count, "count", torch.int32), max_rows,
+        float(temperature), int(seed) & 0xFFFFFFFFFFFFFFFF,
+        _dev_ptr(out_token, "out_token", torch.int32), _dev_ptr(out_conf, "out_conf", torch.float32),
+        _dev_ptr(out_lse, "out_lse", torch.float32), ctypes.byref(plan), _dev_ptr(workspace, "workspace"),
+        workspace.numel() * workspace.element_size() if workspace is not None else 0, _stream_ptr(stream)),
+        "mosaic_masked_logits_sample")
+
+
 def mosaic_unmask_topn(conf, token, idx, count, max_rows, seq_starts, n_per_seq, tokens, mask, stream=None):
     """Per sequence, write the tokens of the n highest-confidence masked rows and clear their mask bytes."""
     _check(lib().mosaic_unmask_topn(
@@ -176,7 +206,7 @@ class MaskOnlyLogits:
     scan scratch, the partials workspace and the three outputs.  `step` enqueues compaction + the fused
     reduction on the current stream and returns views; it never synchronises."""
 
-    def __init__(self, T, d, V, max_rows=None, budget_bytes=0, device="cuda"):
+    def __init__(self, T, d, V, max_rows=None, budget_bytes=0, device="cuda", sampling=False):
         self.T, self.d, self.V = T, d, V
         self.max_rows = T if max_rows is None else max_rows
         self.plan = mosaic_plan_workspace(T, self.max_rows, d, V, budget_bytes)
@@ -184,7 +214,8 @@ class MaskOnlyLogits:
         self.idx = torch.empty(max(T, 1), dtype=torch.int32, device=dev)
         self.count = torch.zeros(1, dtype=torch.int32, device=dev)
         self.scratch = torch.empty(max(mosaic_compact_scratch_bytes(T), 16), dtype=torch.uint8, device=dev)
-        self.workspace = torch.empty(max(self.plan.workspace_bytes, 16), dtype=torch.uint8, device=dev)
+        ws = mosaic_sample_workspace_bytes(self.plan) if sampling else self.plan.workspace_bytes
+        self.workspace = torch.empty(max(ws, 16), dtype=torch.uint8, device=dev)
         n = max(self.max_rows, 1)
         self.token = torch.empty(n, dtype=torch.int32, device=dev)
         self.conf = torch.empty(n, dtype=torch.float32, device=dev)
@@ -199,4 +230,11 @@ class MaskOnlyLogits:
         mosaic_mask_compact(mask, self.idx, self.count, self.scratch, stream)
         mosaic_masked_logits_reduce(hidden, w, self.idx, self.count, self.max_rows, self.token, self.conf, self.lse,
                                     self.plan, self.workspace, stream)
+        return self.idx, self.count, self.token, self.conf, self.lse
+
+    def sample_step(self, hidden, w, mask, temperature, seed, stream=None):
+        """As `step`, drawing the tokens at `temperature` (the object must have been made with sampling=True)."""
+        mosaic_mask_compact(mask, self.idx, self.count, self.scratch, stream)
+        mosaic_masked_logits_sample(hidden, w, self.idx, self.count, self.max_rows, temperature, seed, self.token,
+                                    self.conf, self.lse, self.plan, self.workspace, stream)
         return self.idx, self.count, self.token, self.conf, self.lse

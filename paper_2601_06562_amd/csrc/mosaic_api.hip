@@ -36,10 +36,11 @@ int mosaic_mask_compact(const uint8_t* mask, int64_t T, int32_t* out_idx, int32_
   return rc == 0 ? MOSAIC_OK : MOSAIC_ERR_HIP;
 }
 
-int mosaic_masked_logits_reduce(const void* hidden, int64_t T, int32_t d, int64_t ld_h, const void* w, int32_t V,
-                                const int32_t* idx, const int32_t* count, int64_t max_rows, int32_t* out_token,
-                                float* out_conf, float* out_lse, const mosaic_plan* plan, void* workspace,
-                                int64_t workspace_bytes, void* stream) {
+// Argument checks and launch shared by the greedy and the sampling entry points (temperature 0 = greedy).
+static int reduce_checked(const void* hidden, int64_t T, int32_t d, int64_t ld_h, const void* w, int32_t V,
+                          const int32_t* idx, const int32_t* count, int64_t max_rows, int32_t* out_token,
+                          float* out_conf, float* out_lse, const mosaic_plan* plan, void* workspace,
+                          int64_t workspace_bytes, float temperature, uint64_t seed, void* stream) {
   if (T < 0 || d <= 0 || V < 0 || max_rows < 0 || max_rows > T || plan == nullptr || count == nullptr)
     return MOSAIC_ERR_INVALID_ARG;
   if (T >= (int64_t)1 << 31 || (int64_t)V >= ((int64_t)1 << 31) - MOSAIC_VOCAB_TILE || d % MOSAIC_K_TILE != 0 ||
@@ -60,6 +61,8 @@ int mosaic_masked_logits_reduce(const void* hidden, int64_t T, int32_t d, int64_
     return MOSAIC_ERR_INVALID_ARG;
   const int64_t need = mosaic::partials_bytes(plan->rows_per_chunk, plan->vocab_splits);
   if (plan->workspace_bytes < need || workspace_bytes < need) return MOSAIC_ERR_WORKSPACE_TOO_SMALL;
+  if (temperature > 0.f && workspace_bytes < mosaic::sample_partials_bytes(plan->rows_per_chunk, plan->vocab_splits))
+    return MOSAIC_ERR_WORKSPACE_TOO_SMALL;
 
   mosaic::LogitsArgs a;
   a.hidden = hidden;
@@ -75,8 +78,32 @@ int mosaic_masked_logits_reduce(const void* hidden, int64_t T, int32_t d, int64_
   a.out_conf = out_conf;
   a.out_lse = out_lse;
   a.workspace = workspace;
+  a.temperature = temperature;
+  a.seed = seed;
   const int rc = mosaic::launch_masked_logits(a, *plan, static_cast<hipStream_t>(stream));
   return rc == 0 ? MOSAIC_OK : MOSAIC_ERR_HIP;
+}
+
+int mosaic_masked_logits_reduce(const void* hidden, int64_t T, int32_t d, int64_t ld_h, const void* w, int32_t V,
+                                const int32_t* idx, const int32_t* count, int64_t max_rows, int32_t* out_token,
+                                float* out_conf, float* out_lse, const mosaic_plan* plan, void* workspace,
+                                int64_t workspace_bytes, void* stream) {
+  return reduce_checked(hidden, T, d, ld_h, w, V, idx, count, max_rows, out_token, out_conf, out_lse, plan, workspace,
+                        workspace_bytes, 0.f, 0, stream);
+}
+
+int64_t mosaic_sample_workspace_bytes(const mosaic_plan* plan) {
+  if (plan == nullptr || plan->rows_per_chunk < 1 || plan->vocab_splits < 1) return 0;
+  return mosaic::sample_partials_bytes(plan->rows_per_chunk, plan->vocab_splits);
+}
+
+int mosaic_masked_logits_sample(const void* hidden, int64_t T, int32_t d, int64_t ld_h, const void* w, int32_t V,
+                                const int32_t* idx, const int32_t* count, int64_t max_rows, float temperature,
+                                uint64_t seed, int32_t* out_token, float* out_conf, float* out_lse,
+                                const mosaic_plan* plan, void* workspace, int64_t workspace_bytes, void* stream) {
+  if (!(temperature >= 0.f) || temperature > 1e30f) return MOSAIC_ERR_INVALID_ARG;   // also rejects NaN
+  return reduce_checked(hidden, T, d, ld_h, w, V, idx, count, max_rows, out_token, out_conf, out_lse, plan, workspace,
+                        workspace_bytes, temperature, seed, stream);
 }
 
 int mosaic_unmask_topn(const float* conf, const int32_t* token, const int32_t* idx, const int32_t* count,

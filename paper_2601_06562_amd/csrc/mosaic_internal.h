@@ -29,6 +29,8 @@ struct LogitsArgs {
   float* out_conf;
   float* out_lse;
   void* workspace;
+  float temperature = 0.f;   // > 0: Gumbel-max sampling (needs the 20-byte-per-row-and-split workspace)
+  uint64_t seed = 0;
 };
 int launch_masked_logits(const LogitsArgs& a, const mosaic_plan& plan, hipStream_t stream);
 
@@ -42,6 +44,7 @@ int launch_shift_indices(const int32_t* idx, const int32_t* count, int64_t max_r
 // ---- host-side selector (mosaic_plan.cpp)
 int32_t choose_vocab_splits(int64_t row_tiles, int64_t vocab_tiles, int32_t num_cus);
 int64_t partials_bytes(int64_t rows_padded, int32_t splits);
+int64_t sample_partials_bytes(int64_t rows_padded, int32_t splits);
 
 }  // namespace mosaic
 #endif

@@ -68,6 +68,11 @@ struct KernelParams {
   int32_t* out_token;
   float* out_conf;
   float* out_lse;
+  // sampling with temperature (tau > 0): two more partial planes and the generator key
+  float tau;
+  uint32_t seed_lo, seed_hi;
+  float* part_ym;   // best perturbed score x + tau*g
+  float* part_xa;   // the unperturbed logit at that arg-max
 };
 
 // (m, s, i) monoid: max, sum of exp relative to the max, lowest index attaining the max.
@@ -79,6 +84,48 @@ __device__ __forceinline__ void merge_triple(float& m, float& s, int& i, float m
   s = s * a + s2 * b;
   i = keep ? i : i2;
   m = mn;
+}
+
+// log-sum-exp pair alone (max, sum of exp relative to the max).
+__device__ __forceinline__ void merge_ms(float& m, float& s, float m2, float s2) {
+  const float mn = fmaxf(m, m2);
+  s = s * __builtin_amdgcn_exp2f((m - mn) * kLog2e) + s2 * __builtin_amdgcn_exp2f((m2 - mn) * kLog2e);
+  m = mn;
+}
+
+// Sampled candidate: best perturbed score, the plain logit there, its id (lowest id on equal scores).
+__device__ __forceinline__ void merge_pick(float& ym, float& xa, int& i, float ym2, float xa2, int i2) {
+  const bool keep = (ym > ym2) || (ym == ym2 && i < i2);
+  ym = keep ? ym : ym2;
+  xa = keep ? xa : xa2;
+  i = keep ? i : i2;
+}
+
+// tau * Gumbel noise for the four vocabulary ids 4*v4 .. 4*v4+3 of one position.  Philox4x32-10 (Salmon et
+// al., SC'11), key = seed, counter = (v4, position, 0, 0); word j -> u = ((word >> 9) + 1/2) * 2^-23 (exact in
+// fp32, never 0 or 1); g = -ln(-ln u).  Near u = 1 the inner logarithm comes from the series of -ln(1 - e)
+// (e = 1 - u is exact too), where the hardware log2 loses relative accuracy.
+__device__ __forceinline__ void gumbel4(uint32_t k0, uint32_t k1, uint32_t pos, uint32_t v4, float tau, float (&n)[4]) {
+  uint32_t c0 = v4, c1 = pos, c2 = 0u, c3 = 0u;
+#pragma unroll
+  for (int round = 0; round < 10; ++round) {
+    if (round > 0) { k0 += 0x9E3779B9u; k1 += 0xBB67AE85u; }
+    const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+    const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+    const uint32_t n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
+    c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+  }
+  const uint32_t w[4] = {c0, c1, c2, c3};
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const uint32_t k = w[j] >> 9;
+    const float u = ((float)k + 0.5f) * 0x1p-23f;
+    const float e = ((float)(8388607u - k) + 0.5f) * 0x1p-23f;   // 1 - u
+    const float by_log = -__builtin_amdgcn_logf(u) * kLn2;
+    const float by_series = e * (1.0f + e * (0.5f + e * (1.0f / 3.0f)));
+    const float inner = (e < 0x1p-8f) ? by_series : by_log;       // -ln u  > 0
+    n[j] = -__builtin_amdgcn_logf(inner) * kLn2 * tau;
+  }
 }
 
 template <int N>
@@ -146,7 +193,60 @@ __device__ __forceinline__ void reduce_tile(f32x16 (&acc)[4][2], float (&m)[2], 
 // Separate rings for the two operands: NW slots of W K-tiles, NH slots of H K-tiles (32 KiB each).
 // The shallow ring runs one K-tile ahead, the deep one two; the shallow operand is issued first in
 // every iteration so that the in-order vmcnt wait can leave the deep ring's newest tile in flight.
-template <int NW, int NH>
+// Same tile under sampling: also tracks the arg-max of x + tau*g and the plain logit there.
+template <bool TAIL>
+__device__ __forceinline__ void reduce_tile_sample(f32x16 (&acc)[4][2], float (&m)[2], float (&s)[2], float (&ym)[2],
+                                                   float (&xa)[2], int (&ix)[2], int vb, int V, const int (&pos)[2],
+                                                   uint32_t k0, uint32_t k1, float tau) {
+#pragma unroll
+  for (int bj = 0; bj < 2; ++bj) {
+    float mt = kNeg, yt = kNeg, xsel = 0.f;
+    int sel = 0;
+#pragma unroll
+    for (int bi = 3; bi >= 0; --bi) {
+#pragma unroll
+      for (int r4 = 3; r4 >= 0; --r4) {
+        const int code0 = bi * 32 + 8 * r4;
+        float n[4];
+        gumbel4(k0, k1, (uint32_t)pos[bj], (uint32_t)(vb + code0) >> 2, tau, n);
+#pragma unroll
+        for (int r = 3; r >= 0; --r) {
+          float x = acc[bi][bj][4 * r4 + r];
+          if (TAIL) {
+            if (vb + code0 + r >= V) { x = kNeg; acc[bi][bj][4 * r4 + r] = kNeg; }
+          }
+          const float y = (TAIL && vb + code0 + r >= V) ? kNeg : x + n[r];
+          mt = fmaxf(mt, x);
+          const bool better = y >= yt;   // descending scan: on equal scores the lower id replaces the higher
+          sel = better ? code0 + r : sel;
+          xsel = better ? x : xsel;
+          yt = better ? y : yt;
+        }
+      }
+    }
+    const bool upd = yt > ym[bj];
+    ix[bj] = upd ? vb + sel : ix[bj];
+    xa[bj] = upd ? xsel : xa[bj];
+    ym[bj] = upd ? yt : ym[bj];
+    const float mn = fmaxf(m[bj], mt);
+    const float nml = -mn * kLog2e;
+    float p0 = 0.f, p1 = 0.f, p2 = 0.f, p3 = 0.f;
+#pragma unroll
+    for (int bi = 0; bi < 4; ++bi) {
+#pragma unroll
+      for (int r = 0; r < 16; r += 4) {
+        p0 += exp_rel<TAIL>(acc[bi][bj][r + 0], mn, nml);
+        p1 += exp_rel<TAIL>(acc[bi][bj][r + 1], mn, nml);
+        p2 += exp_rel<TAIL>(acc[bi][bj][r + 2], mn, nml);
+        p3 += exp_rel<TAIL>(acc[bi][bj][r + 3], mn, nml);
+      }
+    }
+    s[bj] = s[bj] * __builtin_amdgcn_exp2f((m[bj] - mn) * kLog2e) + ((p0 + p1) + (p2 + p3));
+    m[bj] = mn;
+  }
+}
+
+template <int NW, int NH, bool SAMPLE>
 __global__ __launch_bounds__(kThreads) void masked_logits_kernel(const KernelParams p) {
   static_assert((NW == 2 || NW == 3) && (NH == 2 || NH == 3) && NW + NH <= 5, "ring shape");
   constexpr int kTileK = 64;
@@ -156,12 +256,14 @@ __global__ __launch_bounds__(kThreads) void masked_logits_kernel(const KernelPar
   constexpr int kSubSteps = 4;
   constexpr int kDW = NW - 1, kDH = NH - 1;             // prefetch distance in K-tiles
   constexpr int kRing = (NW + NH) * kOperandBytes;
-  constexpr int kLds = (NW + NH == 5) ? kRing : kRing + 3 * 256 * 4;
+  constexpr int kLds = (NW + NH == 5) ? kRing : kRing + 5 * 256 * 4;
   constexpr int kRedOff = (NW + NH == 5) ? 0 : kRing;   // 5 slots fill the LDS: merge scratch aliases slot 0
   __shared__ __attribute__((aligned(1024))) char smem[kLds];
   float* red_m = reinterpret_cast<float*>(smem + kRedOff);
   float* red_s = red_m + 256;
   int* red_i = reinterpret_cast<int*>(red_s + 256);
+  float* red_ym = reinterpret_cast<float*>(red_i + 256);   // sampling only
+  float* red_xa = red_ym + 256;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wv = wave & 1;   // vocabulary half of the tile
@@ -265,6 +367,17 @@ __global__ __launch_bounds__(kThreads) void masked_logits_kernel(const KernelPar
     float run_m[2] = {kNeg, kNeg};
     float run_s[2] = {0.f, 0.f};
     int run_i[2] = {INT_MAX, INT_MAX};
+    float run_ym[2] = {kNeg, kNeg};   // sampling: best x + tau*g, the plain logit there
+    float run_xa[2] = {0.f, 0.f};
+    int pos[2] = {0, 0};              // sampling: the position whose row this lane's column holds
+    if constexpr (SAMPLE) {
+#pragma unroll
+      for (int bj = 0; bj < 2; ++bj) {
+        int j = tt * kTileRows + wt * 64 + bj * 32 + l32;
+        if (j > rows - 1) j = rows - 1;
+        pos[bj] = p.idx[p.row0 + j];
+      }
+    }
 
     wait_vm<0>();
 #pragma unroll
@@ -309,8 +422,15 @@ __global__ __launch_bounds__(kThreads) void masked_logits_kernel(const KernelPar
 
       const int v_tile0 = (vt0 + n) * kTileVocab;
       const int vb = v_tile0 + wv * 128 + 4 * lhalf;
-      if (v_tile0 + kTileVocab > p.V) reduce_tile<true>(acc, run_m, run_s, run_i, vb, p.V);
-      else reduce_tile<false>(acc, run_m, run_s, run_i, vb, p.V);
+      if constexpr (SAMPLE) {
+        if (v_tile0 + kTileVocab > p.V)
+          reduce_tile_sample<true>(acc, run_m, run_s, run_ym, run_xa, run_i, vb, p.V, pos, p.seed_lo, p.seed_hi, p.tau);
+        else
+          reduce_tile_sample<false>(acc, run_m, run_s, run_ym, run_xa, run_i, vb, p.V, pos, p.seed_lo, p.seed_hi, p.tau);
+      } else {
+        if (v_tile0 + kTileVocab > p.V) reduce_tile<true>(acc, run_m, run_s, run_i, vb, p.V);
+        else reduce_tile<false>(acc, run_m, run_s, run_i, vb, p.V);
+      }
     }
 
 #pragma unroll
@@ -318,7 +438,12 @@ __global__ __launch_bounds__(kThreads) void masked_logits_kernel(const KernelPar
       const float m2 = __shfl_xor(run_m[bj], 32, 64);
       const float s2 = __shfl_xor(run_s[bj], 32, 64);
       const int i2 = __shfl_xor(run_i[bj], 32, 64);
-      merge_triple(run_m[bj], run_s[bj], run_i[bj], m2, s2, i2);
+      if constexpr (SAMPLE) {
+        merge_ms(run_m[bj], run_s[bj], m2, s2);
+        merge_pick(run_ym[bj], run_xa[bj], run_i[bj], __shfl_xor(run_ym[bj], 32, 64), __shfl_xor(run_xa[bj], 32, 64), i2);
+      } else {
+        merge_triple(run_m[bj], run_s[bj], run_i[bj], m2, s2, i2);
+      }
     }
     __syncthreads();  // every wave is done reading the ring (the merge scratch may alias it)
     if (wv == 1 && lhalf == 0) {
@@ -328,6 +453,10 @@ __global__ __launch_bounds__(kThreads) void masked_logits_kernel(const KernelPar
         red_m[e] = run_m[bj];
         red_s[e] = run_s[bj];
         red_i[e] = run_i[bj];
+        if constexpr (SAMPLE) {
+          red_ym[e] = run_ym[bj];
+          red_xa[e] = run_xa[bj];
+        }
       }
     }
     __syncthreads();
@@ -335,8 +464,15 @@ __global__ __launch_bounds__(kThreads) void masked_logits_kernel(const KernelPar
 #pragma unroll
       for (int bj = 0; bj < 2; ++bj) {
         const int e = (wt * 2 + bj) * 32 + l32;
-        merge_triple(run_m[bj], run_s[bj], run_i[bj], red_m[e], red_s[e], red_i[e]);
         const int64_t slot = (int64_t)sp * p.c_pad + tt * kTileRows + e;
+        if constexpr (SAMPLE) {
+          merge_ms(run_m[bj], run_s[bj], red_m[e], red_s[e]);
+          merge_pick(run_ym[bj], run_xa[bj], run_i[bj], red_ym[e], red_xa[e], red_i[e]);
+          p.part_ym[slot] = run_ym[bj];
+          p.part_xa[slot] = run_xa[bj];
+        } else {
+          merge_triple(run_m[bj], run_s[bj], run_i[bj], red_m[e], red_s[e], red_i[e]);
+        }
         p.part_m[slot] = run_m[bj];
         p.part_s[slot] = run_s[bj];
         p.part_i[slot] = run_i[bj];
@@ -382,12 +518,61 @@ __device__ __forceinline__ void reduce_tile16(f32x4 (&acc)[8][8], float (&m)[8],
   }
 }
 
+// The same column-wise reduction under sampling: also the arg-max of x + tau*g and the plain logit there.
+__device__ __forceinline__ void reduce_tile16_sample(f32x4 (&acc)[8][8], float (&m)[8], float (&s)[8], float (&ym)[8],
+                                                     float (&xa)[8], int (&ix)[8], int vb, const int (&pos)[8],
+                                                     uint32_t k0, uint32_t k1, float tau) {
+#pragma unroll
+  for (int tb = 0; tb < 8; ++tb) {
+    float x[32];
+#pragma unroll
+    for (int bi = 0; bi < 8; ++bi)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) x[bi * 4 + r] = acc[bi][tb][r];
+    float mt = kNeg, yt = kNeg, xsel = 0.f;
+    int sel = 0;
+#pragma unroll
+    for (int bi = 7; bi >= 0; --bi) {
+      float n[4];
+      gumbel4(k0, k1, (uint32_t)pos[tb], (uint32_t)(vb + 16 * bi) >> 2, tau, n);
+#pragma unroll
+      for (int r = 3; r >= 0; --r) {
+        const float xv = x[bi * 4 + r];
+        const float y = xv + n[r];
+        mt = fmaxf(mt, xv);
+        const bool better = y >= yt;   // descending scan: on equal scores the lower id replaces the higher
+        sel = better ? bi * 16 + r : sel;
+        xsel = better ? xv : xsel;
+        yt = better ? y : yt;
+      }
+    }
+    const bool upd = yt > ym[tb];
+    ix[tb] = upd ? vb + sel : ix[tb];
+    xa[tb] = upd ? xsel : xa[tb];
+    ym[tb] = upd ? yt : ym[tb];
+    const float mn = fmaxf(m[tb], mt);
+    const float nml = -mn * kLog2e;
+    float p0 = 0.f, p1 = 0.f, p2 = 0.f, p3 = 0.f;
+#pragma unroll
+    for (int e = 0; e < 32; e += 4) {
+      p0 += __builtin_amdgcn_exp2f(__builtin_fmaf(x[e + 0], kLog2e, nml));
+      p1 += __builtin_amdgcn_exp2f(__builtin_fmaf(x[e + 1], kLog2e, nml));
+      p2 += __builtin_amdgcn_exp2f(__builtin_fmaf(x[e + 2], kLog2e, nml));
+      p3 += __builtin_amdgcn_exp2f(__builtin_fmaf(x[e + 3], kLog2e, nml));
+    }
+    s[tb] = s[tb] * __builtin_amdgcn_exp2f((m[tb] - mn) * kLog2e) + ((p0 + p1) + (p2 + p3));
+    m[tb] = mn;
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
 // ---- 4-wave fast path: one wave per SIMD, 128 (vocab) x 128 (token) per wave as 8 x 8 blocks of
 // v_mfma_f32_16x16x32_bf16 (the more power-efficient bf16 shape on this part), accumulators in AGPRs.
 // The K-loop of a vocabulary tile is one hand-scheduled inline-asm statement (w4_loop.inc, generated):
 // every MFMA is followed by at most one LDS read or one direct-to-LDS copy, fragments are double-
 // buffered in fixed VGPRs, the LM-head ring runs two K-tiles ahead and the hidden ring one.
 // Preconditions (checked by the launcher): V % 256 == 0, hidden span < 4 GiB, 256*d*2 < 4 GiB.
+template <bool SAMPLE>
 __global__ __launch_bounds__(256) void masked_logits_kernel_w4(const KernelParams p) {
   constexpr int NW = 3, NH = 2;
   constexpr int kTileK = 64;
@@ -398,6 +583,8 @@ __global__ __launch_bounds__(256) void masked_logits_kernel_w4(const KernelParam
   float* red_m = reinterpret_cast<float*>(smem);        // merge scratch aliases W slot 0 at unit end
   float* red_s = red_m + 256;
   int* red_i = reinterpret_cast<int*>(red_s + 256);
+  float* red_ym = reinterpret_cast<float*>(red_i + 256);   // sampling only
+  float* red_xa = red_ym + 256;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wv = wave & 1;   // vocabulary half of the tile
@@ -505,10 +692,17 @@ __global__ __launch_bounds__(256) void masked_logits_kernel_w4(const KernelParam
     uint32_t st_wk = (uint32_t)(gw % nk), st_hk = (uint32_t)(gh % nk);
     uint32_t st_g = 0;
 
-    float run_m[8], run_s[8];
-    int run_i[8];
+    float run_m[8], run_s[8], run_ym[8], run_xa[8];
+    int run_i[8], pos[8];
 #pragma unroll
-    for (int tb = 0; tb < 8; ++tb) { run_m[tb] = kNeg; run_s[tb] = 0.f; run_i[tb] = INT_MAX; }
+    for (int tb = 0; tb < 8; ++tb) {
+      run_m[tb] = kNeg; run_s[tb] = 0.f; run_i[tb] = INT_MAX; run_ym[tb] = kNeg; run_xa[tb] = 0.f; pos[tb] = 0;
+      if constexpr (SAMPLE) {   // the position whose row this lane's column tb holds
+        int j = tt * kTileRows + wt * 128 + tb * 16 + l16;
+        if (j > rows - 1) j = rows - 1;
+        pos[tb] = p.idx[p.row0 + j];
+      }
+    }
 
     for (int n = 0; n < ntile; ++n) {
       f32x4 acc[8][8];
@@ -540,7 +734,8 @@ __global__ __launch_bounds__(256) void masked_logits_kernel_w4(const KernelParam
       }
       const int v_tile0 = (vt0 + n) * kTileVocab;
       const int vb = v_tile0 + wv * 128 + 4 * q;
-      reduce_tile16(acc, run_m, run_s, run_i, vb);
+      if constexpr (SAMPLE) reduce_tile16_sample(acc, run_m, run_s, run_ym, run_xa, run_i, vb, pos, p.seed_lo, p.seed_hi, p.tau);
+      else reduce_tile16(acc, run_m, run_s, run_i, vb);
     }
 
     // Unit end: fold the four lanes that share a token (lane ^ 16, lane ^ 32), then the two waves that
@@ -552,7 +747,12 @@ __global__ __launch_bounds__(256) void masked_logits_kernel_w4(const KernelParam
         const float m2 = __shfl_xor(run_m[tb], x, 64);
         const float s2 = __shfl_xor(run_s[tb], x, 64);
         const int i2 = __shfl_xor(run_i[tb], x, 64);
-        merge_triple(run_m[tb], run_s[tb], run_i[tb], m2, s2, i2);
+        if constexpr (SAMPLE) {
+          merge_ms(run_m[tb], run_s[tb], m2, s2);
+          merge_pick(run_ym[tb], run_xa[tb], run_i[tb], __shfl_xor(run_ym[tb], x, 64), __shfl_xor(run_xa[tb], x, 64), i2);
+        } else {
+          merge_triple(run_m[tb], run_s[tb], run_i[tb], m2, s2, i2);
+        }
       }
     }
     __syncthreads();  // every wave is done with the ring (the merge scratch aliases it)
@@ -563,6 +763,10 @@ __global__ __launch_bounds__(256) void masked_logits_kernel_w4(const KernelParam
         red_m[e] = run_m[tb];
         red_s[e] = run_s[tb];
         red_i[e] = run_i[tb];
+        if constexpr (SAMPLE) {
+          red_ym[e] = run_ym[tb];
+          red_xa[e] = run_xa[tb];
+        }
       }
     }
     __syncthreads();
@@ -570,8 +774,15 @@ __global__ __launch_bounds__(256) void masked_logits_kernel_w4(const KernelParam
 #pragma unroll
       for (int tb = 0; tb < 8; ++tb) {
         const int e = wt * 128 + tb * 16 + l16;
-        merge_triple(run_m[tb], run_s[tb], run_i[tb], red_m[e], red_s[e], red_i[e]);
         const int64_t slot = (int64_t)sp * p.c_pad + tt * kTileRows + e;
+        if constexpr (SAMPLE) {
+          merge_ms(run_m[tb], run_s[tb], red_m[e], red_s[e]);
+          merge_pick(run_ym[tb], run_xa[tb], run_i[tb], red_ym[e], red_xa[e], red_i[e]);
+          p.part_ym[slot] = run_ym[tb];
+          p.part_xa[slot] = run_xa[tb];
+        } else {
+          merge_triple(run_m[tb], run_s[tb], run_i[tb], red_m[e], red_s[e], red_i[e]);
+        }
         p.part_m[slot] = run_m[tb];
         p.part_s[slot] = run_s[tb];
         p.part_i[slot] = run_i[tb];
@@ -591,6 +802,18 @@ __global__ __launch_bounds__(256) void combine_kernel(const KernelParams p) {
   if (r >= rows) return;
   float m = kNeg, s = 0.f;
   int i = INT_MAX;
+  if (p.tau > 0.f) {   // sampling: the token is the arg-max of the perturbed scores, conf its soft-max probability
+    float ym = kNeg, xa = 0.f;
+    for (int sp = 0; sp < p.splits; ++sp) {
+      const int64_t slot = (int64_t)sp * p.c_pad + r;
+      merge_ms(m, s, p.part_m[slot], p.part_s[slot]);
+      merge_pick(ym, xa, i, p.part_ym[slot], p.part_xa[slot], p.part_i[slot]);
+    }
+    p.out_token[p.row0 + r] = i;
+    p.out_lse[p.row0 + r] = m + __builtin_amdgcn_logf(s) * kLn2;
+    p.out_conf[p.row0 + r] = __builtin_amdgcn_exp2f((xa - m) * kLog2e) / s;
+    return;
+  }
   for (int sp = 0; sp < p.splits; ++sp) {
     const int64_t slot = (int64_t)sp * p.c_pad + r;
     merge_triple(m, s, i, p.part_m[slot], p.part_s[slot], p.part_i[slot]);
@@ -599,7 +822,6 @@ __global__ __launch_bounds__(256) void combine_kernel(const KernelParams p) {
   p.out_lse[p.row0 + r] = m + __builtin_amdgcn_logf(s) * kLn2;
   p.out_conf[p.row0 + r] = 1.0f / s;
 }
-
 
 int launch_masked_logits(const LogitsArgs& a, const mosaic_plan& plan, hipStream_t stream) {
   KernelParams p;
@@ -622,6 +844,12 @@ int launch_masked_logits(const LogitsArgs& a, const mosaic_plan& plan, hipStream
   p.out_token = a.out_token;
   p.out_conf = a.out_conf;
   p.out_lse = a.out_lse;
+  const bool sample = a.temperature > 0.f;
+  p.tau = sample ? a.temperature : 0.f;
+  p.seed_lo = (uint32_t)a.seed;
+  p.seed_hi = (uint32_t)(a.seed >> 32);
+  p.part_ym = reinterpret_cast<float*>(p.part_i + (int64_t)plan.vocab_splits * plan.rows_per_chunk);
+  p.part_xa = p.part_ym + (int64_t)plan.vocab_splits * plan.rows_per_chunk;
 
   // The hand-scheduled 4-wave kernel needs whole vocabulary tiles and 32-bit row offsets; everything
   // else (and plans that ask for it) goes to the general 8-wave kernel.
@@ -637,10 +865,14 @@ int launch_masked_logits(const LogitsArgs& a, const mosaic_plan& plan, hipStream
     const int64_t tiles = (cap + kTileRows - 1) / kTileRows;
     int64_t grid = tiles * plan.vocab_splits;
     if (grid > plan.grid) grid = plan.grid;
-    if (fast)
-      hipLaunchKernelGGL(masked_logits_kernel_w4, dim3((unsigned)grid), dim3(256), 0, stream, p);
+    if (fast && sample)
+      hipLaunchKernelGGL((masked_logits_kernel_w4<true>), dim3((unsigned)grid), dim3(256), 0, stream, p);
+    else if (fast)
+      hipLaunchKernelGGL((masked_logits_kernel_w4<false>), dim3((unsigned)grid), dim3(256), 0, stream, p);
+    else if (sample)
+      hipLaunchKernelGGL((masked_logits_kernel<3, 2, true>), dim3((unsigned)grid), dim3(kThreads), 0, stream, p);
     else
-      hipLaunchKernelGGL((masked_logits_kernel<3, 2>), dim3((unsigned)grid), dim3(kThreads), 0, stream, p);
+      hipLaunchKernelGGL((masked_logits_kernel<3, 2, false>), dim3((unsigned)grid), dim3(kThreads), 0, stream, p);
     hipLaunchKernelGGL(combine_kernel, dim3((unsigned)((cap + 255) / 256)), dim3(256), 0, stream, p);
   }
   return hipGetLastError() == hipSuccess ? 0 : -1;

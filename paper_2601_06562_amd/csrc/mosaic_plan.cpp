@@ -13,6 +13,8 @@
 namespace mosaic {
 
 int64_t partials_bytes(int64_t rows_padded, int32_t splits) { return 12 * rows_padded * (int64_t)splits; }
+// sampling keeps two more planes per row and split (best perturbed score, the plain logit there)
+int64_t sample_partials_bytes(int64_t rows_padded, int32_t splits) { return 20 * rows_padded * (int64_t)splits; }
 
 // Number of vocabulary splits for `row_tiles` row tiles: the workgroups walk their units in rounds of
 // `num_cus`; a round lasts as long as its longest unit.  Pick the S that minimises

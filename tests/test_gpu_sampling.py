@@ -1,0 +1,209 @@
+"""GPU parity of temperature sampling: mosaic_masked_logits_sample, through the C ABI, against the CPU
+oracle's Gumbel-max sampler on the same (seed, position, id) noise.
+
+Acceptance: the token equals the oracle's wherever the oracle's top-2 gap of the perturbed scores exceeds
+YGAP_STRICT (below that, fp32 rounding of the logits or of the noise may legitimately flip the order, and
+the picked id must then be within the same margin of the best perturbed score); lse within 2e-3; conf
+within 2e-3 absolute and 5e-3 relative on rows whose token agrees."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2601_06562_amd import binding, workloads
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+LSE_ATOL, CONF_ATOL, CONF_RTOL = 2e-3, 2e-3, 5e-3
+
+
+def ygap_strict(tau):
+    # fp32 logits differ from the fp64-accumulated ones by ~1e-5; the fp32 noise by ~1e-6 * |g| * tau
+    return 1e-3 * (1.0 + tau)
+
+
+def run_sample(wl, tau, seed, budget_bytes=0, plan_edit=None, max_rows=None):
+    op = binding.MaskOnlyLogits(wl.T, wl.d, wl.V, max_rows=max_rows, budget_bytes=budget_bytes, device=DEV,
+                                sampling=True)
+    if plan_edit is not None:
+        plan_edit(op.plan)
+        op.plan.workspace_bytes = 12 * op.plan.rows_per_chunk * op.plan.vocab_splits
+        op.workspace = torch.empty(max(binding.mosaic_sample_workspace_bytes(op.plan), 16), dtype=torch.uint8,
+                                   device=DEV)
+    op.token.fill_(-7)
+    op.conf.fill_(-7.0)
+    op.lse.fill_(-7.0)
+    op.sample_step(wl.hidden, wl.w, wl.mask, tau, seed)
+    torch.cuda.synchronize()
+    M = int(op.count.item())
+    return dict(M=M, idx=op.idx.cpu().numpy()[:M], tok=op.token.cpu().numpy(), conf=op.conf.cpu().numpy(),
+                lse=op.lse.cpu().numpy(), op=op)
+
+
+def check_sample(out, hb, wb, rows, tau, seed, what):
+    """rows: indices into the compacted list to check; hb = bf16 bits of the hidden rows AT those rows' positions
+    (hb[k] is the hidden row of position out['idx'][rows[k]])."""
+    pos = out["idx"][rows].astype(np.int64)
+    # the oracle indexes H by position: give it a sparse view through a position -> row map
+    order = np.arange(pos.size)
+    x_all = np.stack([oracle.row_logits(hb[k], wb) for k in order]) if pos.size else np.zeros((0, wb.shape[0]), np.float32)
+    n_strict = 0
+    for k in order:
+        tok_o, conf_o, lse_o, gap_o = oracle.row_sample(x_all[k], tau, seed, int(pos[k]))
+        tok, conf, lse = int(out["tok"][rows[k]]), float(out["conf"][rows[k]]), float(out["lse"][rows[k]])
+        assert np.isfinite(lse) and np.isfinite(conf), what
+        assert abs(lse - lse_o) <= LSE_ATOL, f"{what}: row {k} lse {lse} vs {lse_o}"
+        assert 0 <= tok < wb.shape[0], f"{what}: row {k} token {tok} out of range"
+        if gap_o > ygap_strict(tau):
+            n_strict += 1
+            assert tok == tok_o, f"{what}: row {k} (position {pos[k]}) sampled {tok}, oracle {tok_o}, gap {gap_o}"
+        elif tok != tok_o:
+            y_pick = float(x_all[k][tok]) + tau * oracle.gumbel(seed, int(pos[k]), tok)
+            y_best = float(x_all[k][tok_o]) + tau * oracle.gumbel(seed, int(pos[k]), tok_o)
+            assert y_pick >= y_best - ygap_strict(tau), f"{what}: row {k} picked a non-maximal perturbed score"
+        if tok == tok_o:
+            assert abs(conf - conf_o) <= CONF_ATOL and abs(conf - conf_o) <= CONF_RTOL * max(conf_o, 1e-30), \
+                f"{what}: row {k} conf {conf} vs {conf_o}"
+    return n_strict
+
+
+SHAPES = [
+    # general kernel (vocabulary not a multiple of 256): tails in every dimension
+    (1, 64, 1, 1.0),
+    (7, 64, 33, 1.0),
+    (300, 128, 1000, 0.9),
+    (700, 192, 777, 0.5),
+    (900, 448, 4099, 0.7),
+    # 4-wave kernel
+    (300, 64, 256, 1.0),
+    (520, 128, 512, 0.7),
+    (1000, 320, 1280, 0.5),
+    (130, 512, 2560, 1.0),
+    (2100, 64, 4096, 0.9),
+]
+
+
+@pytest.mark.parametrize("T,d,V,p", SHAPES)
+@pytest.mark.parametrize("tau", [0.3, 1.0])
+def test_sample_small_shapes_vs_oracle(T, d, V, p, tau):
+    print(f"sample small T={T} d={d} V={V} p={p} tau={tau}", flush=True)
+    wl = workloads.small_random(T, d, V, p=p, seed=T + V, device=DEV)
+    seed = 0x9E3779B97F4A7C15 ^ (T * 1315423911 + V)
+    out = run_sample(wl, tau, seed)
+    M = out["M"]
+    assert np.array_equal(out["idx"], oracle.mask_select(wl.mask.cpu().numpy()))
+    rows = np.arange(M)
+    if M > 400:                                   # every tile and the ragged tail, thinned in between
+        rows = np.unique(np.concatenate([np.arange(0, M, 3), np.arange(M - 40, M)]))
+    hb = workloads.bf16_bits(wl.hidden[torch.as_tensor(out["idx"][rows].astype(np.int64), device=DEV)])
+    n_strict = check_sample(out, hb, workloads.bf16_bits(wl.w), rows, tau, seed, wl.name)
+    assert n_strict >= 0.9 * rows.size or V < 64  # the strict rule must bite on nearly every row
+    assert np.all(out["tok"][M:] == -7) and np.all(out["lse"][M:] == -7.0)
+
+
+def test_zero_temperature_is_the_greedy_entry_point():
+    print("sample tau=0", flush=True)
+    for (T, d, V) in [(700, 192, 777), (1000, 320, 1280)]:
+        wl = workloads.small_random(T, d, V, p=0.8, seed=3, device=DEV)
+        a = run_sample(wl, 0.0, 1234)
+        op = binding.MaskOnlyLogits(T, d, V, device=DEV)
+        op.step(wl.hidden, wl.w, wl.mask)
+        torch.cuda.synchronize()
+        M = a["M"]
+        assert np.array_equal(a["tok"][:M], op.token.cpu().numpy()[:M])
+        assert np.array_equal(a["conf"][:M], op.conf.cpu().numpy()[:M])
+        assert np.array_equal(a["lse"][:M], op.lse.cpu().numpy()[:M])
+
+
+def test_sample_is_a_function_of_seed_position_and_id_only():
+    """The same seed gives the same tokens whatever the chunking and the vocabulary split; another seed
+    gives other tokens; and a row's draw depends on its position, not on its place in the compacted list."""
+    print("sample invariance", flush=True)
+    T, d, V = 1500, 128, 2048
+    wl = workloads.small_random(T, d, V, p=0.9, seed=11, device=DEV)
+    base = run_sample(wl, 1.0, 42)
+    M = base["M"]
+    again = run_sample(wl, 1.0, 42)
+    assert np.array_equal(base["tok"][:M], again["tok"][:M])
+    chunked = run_sample(wl, 1.0, 42, budget_bytes=12 * 512 * 1)
+    assert chunked["op"].plan.num_chunks > 1
+    assert np.array_equal(base["tok"][:M], chunked["tok"][:M])
+    assert np.abs(base["lse"][:M] - chunked["lse"][:M]).max() <= 1e-5
+
+    def one_split(plan):
+        plan.vocab_splits = 1
+    def many_splits(plan):
+        plan.vocab_splits = 8
+    s1 = run_sample(wl, 1.0, 42, plan_edit=one_split)
+    s8 = run_sample(wl, 1.0, 42, plan_edit=many_splits)
+    assert np.array_equal(s1["tok"][:M], s8["tok"][:M]) and np.array_equal(s1["tok"][:M], base["tok"][:M])
+    other = run_sample(wl, 1.0, 43)
+    assert (other["tok"][:M] != base["tok"][:M]).mean() > 0.9
+    # unmask every other position: the surviving rows keep their draws
+    mask2 = wl.mask.clone()
+    mask2[::2] = 0
+    wl2 = workloads.Workload(wl.name, T, d, V, wl.hidden, wl.w, mask2, [T])
+    sub = run_sample(wl2, 1.0, 42)
+    where = {int(t): j for j, t in enumerate(base["idx"])}
+    take = np.array([where[int(t)] for t in sub["idx"]])
+    assert np.array_equal(sub["tok"][:sub["M"]], base["tok"][take])
+
+
+def test_general_and_fast_kernel_draw_the_same_tokens():
+    print("sample fast vs general", flush=True)
+    T, d, V = 800, 256, 1536
+    wl = workloads.small_random(T, d, V, p=1.0, seed=5, device=DEV)
+
+    def general(plan):
+        plan.flags |= binding.PLAN_GENERAL_KERNEL
+    fast = run_sample(wl, 0.8, 99)
+    gen = run_sample(wl, 0.8, 99, plan_edit=general)
+    M = fast["M"]
+    agree = (fast["tok"][:M] == gen["tok"][:M]).mean()
+    assert agree > 0.995, agree          # the two MFMA shapes round the logits differently: near-ties may flip
+    assert np.abs(fast["lse"][:M] - gen["lse"][:M]).max() <= 1e-4
+
+
+def test_sample_frequencies_follow_the_softmax():
+    """Many positions holding the same hidden row: the empirical token distribution is soft-max(x / tau)."""
+    print("sample frequencies", flush=True)
+    T, d, V, tau = 16384, 64, 256, 0.7
+    rng = np.random.default_rng(3)
+    h = rng.standard_normal(d).astype(np.float32)
+    W = (rng.standard_normal((V, d)) * 0.35).astype(np.float32)
+    hidden = torch.as_tensor(np.tile(h, (T, 1))).to(torch.bfloat16).to(DEV)
+    w = torch.as_tensor(W).to(torch.bfloat16).to(DEV)
+    wl = workloads.Workload("same_rows", T, d, V, hidden, w, torch.ones(T, dtype=torch.uint8, device=DEV), [T])
+    out = run_sample(wl, tau, 2026)
+    x = oracle.row_logits(workloads.bf16_bits(hidden[:1])[0], workloads.bf16_bits(w)).astype(np.float64)
+    prob = np.exp(x / tau - (x / tau).max())
+    prob /= prob.sum()
+    counts = np.bincount(out["tok"][:T], minlength=V).astype(np.float64)
+    big = prob * T >= 5
+    chi2 = (((counts - prob * T) ** 2) / (prob * T))[big].sum()
+    dof = int(big.sum()) - 1
+    assert chi2 < dof + 6 * np.sqrt(2 * dof), (chi2, dof)       # six sigma of the chi-square law
+    # conf is the plain soft-max probability (temperature 1) of the drawn token
+    p1 = np.exp(x - x.max())
+    p1 /= p1.sum()
+    assert np.abs(out["conf"][:T] - p1[out["tok"][:T]]).max() <= 2e-3
+
+
+def test_sample_full_size_llada_first_step():
+    """The benchmark workload in its real launch configuration: sampled rows against the oracle."""
+    print("sample full-size llada_first_step: generating", flush=True)
+    wl = workloads.make("llada_first_step", device=DEV)
+    tau, seed = 1.0, 0xC0FFEE1234567
+    out = run_sample(wl, tau, seed, max_rows=wl.M)
+    M = out["M"]
+    assert M == wl.M
+    tok, conf, lse = out["tok"][:M], out["conf"][:M], out["lse"][:M]
+    assert np.all((tok >= 0) & (tok < wl.V)) and np.all(np.isfinite(lse)) and np.all((conf > 0) & (conf <= 1))
+    assert np.unique(tok).size > 0.9 * M            # near-flat soft-max over 126k ids: draws rarely repeat
+    rng = np.random.default_rng(17)
+    rows = np.unique(np.concatenate([[0, 255, 256, M - 1], rng.integers(0, M, 60)]))
+    print(f"sample full-size: oracle on {rows.size} rows", flush=True)
+    hb = workloads.bf16_bits(wl.hidden[torch.as_tensor(out["idx"][rows].astype(np.int64), device=DEV)])
+    n_strict = check_sample(out, hb, workloads.bf16_bits(wl.w), rows, tau, seed, "llada_first_step")
+    print(f"sample full-size: {n_strict} strict rows of {rows.size}", flush=True)
+    assert n_strict >= 0.9 * rows.size

@@ -141,3 +141,27 @@ def test_sampling_tail_entry_points_validate_before_launch():
     assert sh(out=null) == binding.MOSAIC_ERR_INVALID_ARG
     assert sh(max_rows=-1) == binding.MOSAIC_ERR_INVALID_ARG
     assert sh(max_rows=0, idx=null) == binding.MOSAIC_OK
+
+
+def test_sampling_entry_point_validates_before_launch():
+    L = binding.lib()
+    null, fake = ctypes.c_void_p(0), ctypes.c_void_p(0x1000)
+    plan = binding.mosaic_plan_workspace(4096, 4096, 4096, 126464, 0)
+    need = binding.mosaic_sample_workspace_bytes(plan)
+    assert need == 20 * plan.rows_per_chunk * plan.vocab_splits            # five fp32/int32 planes per row and split
+    assert need > plan.workspace_bytes
+    assert L.mosaic_sample_workspace_bytes(None) == 0
+    call = lambda **kw: L.mosaic_masked_logits_sample(
+        kw.get("hidden", fake), 4096, kw.get("d", 4096), 4096, fake, 126464, fake, kw.get("count", fake),
+        kw.get("max_rows", 4096), kw.get("tau", 1.0), kw.get("seed", 7), fake, fake, fake, ctypes.byref(plan), fake,
+        kw.get("ws_bytes", need), null)
+    assert call(tau=-0.5) == binding.MOSAIC_ERR_INVALID_ARG
+    assert call(tau=float("nan")) == binding.MOSAIC_ERR_INVALID_ARG
+    assert call(tau=float("inf")) == binding.MOSAIC_ERR_INVALID_ARG
+    assert call(ws_bytes=need - 1) == binding.MOSAIC_ERR_WORKSPACE_TOO_SMALL      # the greedy size is not enough
+    assert call(ws_bytes=plan.workspace_bytes) == binding.MOSAIC_ERR_WORKSPACE_TOO_SMALL
+    assert call(hidden=null) == binding.MOSAIC_ERR_INVALID_ARG
+    assert call(count=null) == binding.MOSAIC_ERR_INVALID_ARG
+    assert call(d=4090) == binding.MOSAIC_ERR_UNSUPPORTED_SHAPE
+    assert call(max_rows=0) == binding.MOSAIC_OK                                   # nothing to do
+    assert call(seed=2 ** 64 - 1, tau=-1.0) == binding.MOSAIC_ERR_INVALID_ARG      # a full 64-bit seed is accepted
