@@ -190,6 +190,20 @@ int mosaic_unmask_topn(const float *conf, const int32_t *token, const int32_t *i
 int mosaic_shift_indices(const int32_t *idx, const int32_t *count, int64_t max_rows, const int32_t *seq_starts,
                          int32_t num_seqs, int32_t *out_gather, void *stream);
 
+/*
+ * Measurement aid, not part of the method: a register-only loop of the bf16 matrix instruction the fused
+ * kernel is built on (v_mfma_f32_16x16x32_bf16, the kernel's own 8 x 8 accumulator grid, one wave per SIMD,
+ * no memory traffic inside the loop).  Its rate is what the matrix cores sustain at the clock the chip
+ * settles to under that load; bench.py reports the fused kernel against it as well as against the datasheet
+ * peak.  Each of num_wgs workgroups (256 threads) issues iters x 4 x 64 instructions;
+ * mosaic_mfma_probe_flops returns the flops of one launch (0 for negative arguments).
+ *   operands   dev, 64 KiB of finite bf16 values, 16-byte aligned (read once)
+ *   sink       dev float[65536]; overwritten with values of no interest
+ * Errors: INVALID_ARG (null or misaligned pointer, iters outside [1, 2^20], num_wgs outside [1, 65536]), HIP.
+ */
+int64_t mosaic_mfma_probe_flops(int32_t iters, int32_t num_wgs);
+int mosaic_mfma_probe(const void *operands, float *sink, int32_t iters, int32_t num_wgs, void *stream);
+
 /* Library version, "major.minor" as major*1000 + minor. */
 int mosaic_version(void);
 

@@ -27,7 +27,7 @@ PLAN_GENERAL_KERNEL = 1   # plan.flags bit: force the general 8-wave kernel
 
 EXPORTS = (
     "mosaic_status_string", "mosaic_plan_workspace", "mosaic_compact_scratch_bytes", "mosaic_mask_compact",
-    "mosaic_masked_logits_reduce", "mosaic_sample_workspace_bytes", "mosaic_masked_logits_sample", "mosaic_unmask_topn", "mosaic_shift_indices", "mosaic_version",
+    "mosaic_masked_logits_reduce", "mosaic_sample_workspace_bytes", "mosaic_masked_logits_sample", "mosaic_unmask_topn", "mosaic_shift_indices", "mosaic_mfma_probe_flops", "mosaic_mfma_probe", "mosaic_version",
 )
 
 
@@ -88,6 +88,10 @@ def lib():
         L.mosaic_unmask_topn.argtypes = [p, p, p, p, i64, p, i32, p, p, p, i64, p]
         L.mosaic_shift_indices.restype = ctypes.c_int
         L.mosaic_shift_indices.argtypes = [p, p, i64, p, i32, p, p]
+        L.mosaic_mfma_probe_flops.restype = i64
+        L.mosaic_mfma_probe_flops.argtypes = [i32, i32]
+        L.mosaic_mfma_probe.restype = ctypes.c_int
+        L.mosaic_mfma_probe.argtypes = [p, p, i32, i32, p]
         _lib = L
     return _lib
 
@@ -199,6 +203,15 @@ def mosaic_shift_indices(idx, count, max_rows, seq_starts, out_gather, stream=No
         _dev_ptr(idx, "idx", torch.int32), _dev_ptr(count, "count", torch.int32), max_rows,
         _dev_ptr(seq_starts, "seq_starts", torch.int32), seq_starts.numel() - 1,
         _dev_ptr(out_gather, "out_gather", torch.int32), _stream_ptr(stream)), "mosaic_shift_indices")
+
+
+def mosaic_mfma_probe(operands, sink, iters, num_wgs, stream=None) -> int:
+    """Enqueue the register-only MFMA loop (a measurement aid); returns the flops of the launch."""
+    if operands.numel() * operands.element_size() < 65536 or sink.numel() < 65536:
+        raise ValueError("operands must hold 64 KiB, sink 65536 floats")
+    _check(lib().mosaic_mfma_probe(_dev_ptr(operands, "operands", torch.bfloat16), _dev_ptr(sink, "sink", torch.float32),
+                                   int(iters), int(num_wgs), _stream_ptr(stream)), "mosaic_mfma_probe")
+    return int(lib().mosaic_mfma_probe_flops(int(iters), int(num_wgs)))
 
 
 class MaskOnlyLogits:

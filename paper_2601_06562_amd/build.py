@@ -9,7 +9,8 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libmosaic.so")
-SOURCES = ["mosaic_api.hip", "mosaic_compact.hip", "mosaic_logits.hip", "mosaic_unmask.hip", "mosaic_plan.cpp"]
+SOURCES = ["mosaic_api.hip", "mosaic_compact.hip", "mosaic_logits.hip", "mosaic_unmask.hip", "mosaic_probe.hip",
+           "mosaic_plan.cpp"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

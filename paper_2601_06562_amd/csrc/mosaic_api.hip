@@ -106,6 +106,19 @@ int mosaic_masked_logits_sample(const void* hidden, int64_t T, int32_t d, int64_
                         workspace_bytes, temperature, seed, stream);
 }
 
+int64_t mosaic_mfma_probe_flops(int32_t iters, int32_t num_wgs) {
+  if (iters < 0 || num_wgs < 0) return 0;
+  return (int64_t)num_wgs * 4 * 64 * 16384 * (int64_t)iters;   // 4 waves, 64 instructions of 16*16*32*2 flop
+}
+
+int mosaic_mfma_probe(const void* operands, float* sink, int32_t iters, int32_t num_wgs, void* stream) {
+  if (operands == nullptr || sink == nullptr || iters < 1 || iters > (1 << 20) || num_wgs < 1 || num_wgs > 65536 ||
+      (reinterpret_cast<uintptr_t>(operands) & 15u))
+    return MOSAIC_ERR_INVALID_ARG;
+  const int rc = mosaic::launch_mfma_probe(operands, sink, iters, num_wgs, static_cast<hipStream_t>(stream));
+  return rc == 0 ? MOSAIC_OK : MOSAIC_ERR_HIP;
+}
+
 int mosaic_unmask_topn(const float* conf, const int32_t* token, const int32_t* idx, const int32_t* count,
                        int64_t max_rows, const int32_t* seq_starts, int32_t num_seqs, const int32_t* n_per_seq,
                        int32_t* tokens, uint8_t* mask, int64_t T, void* stream) {

@@ -41,6 +41,9 @@ int launch_unmask_topn(const float* conf, const int32_t* token, const int32_t* i
 int launch_shift_indices(const int32_t* idx, const int32_t* count, int64_t max_rows, const int32_t* seq_starts,
                          int32_t num_seqs, int32_t* gather, hipStream_t stream);
 
+// ---- measurement aid (mosaic_probe.hip)
+int launch_mfma_probe(const void* operands, float* sink, int32_t iters, int32_t num_wgs, hipStream_t stream);
+
 // ---- host-side selector (mosaic_plan.cpp)
 int32_t choose_vocab_splits(int64_t row_tiles, int64_t vocab_tiles, int32_t num_cus);
 int64_t partials_bytes(int64_t rows_padded, int32_t splits);

@@ -273,3 +273,13 @@ def test_strided_hidden_rows():
     b = run_hip(wide[:, :128], wl.w, wl.mask)
     for k in ("tok", "conf", "lse"):
         assert np.array_equal(a[k], b[k]), k
+
+
+def test_mfma_probe_runs_and_reports_its_flops():
+    print("mfma probe", flush=True)
+    operands = (torch.rand(32768, device=DEV) - 0.5).to(torch.bfloat16)
+    sink = torch.full((65536,), float("nan"), dtype=torch.float32, device=DEV)
+    flop = binding.mosaic_mfma_probe(operands, sink, 100, 256)
+    torch.cuda.synchronize()
+    assert flop == 100 * 256 * 4 * 64 * 16384
+    assert bool(torch.isfinite(sink).all())            # every lane of every workgroup stored its sum

@@ -165,3 +165,16 @@ def test_sampling_entry_point_validates_before_launch():
     assert call(d=4090) == binding.MOSAIC_ERR_UNSUPPORTED_SHAPE
     assert call(max_rows=0) == binding.MOSAIC_OK                                   # nothing to do
     assert call(seed=2 ** 64 - 1, tau=-1.0) == binding.MOSAIC_ERR_INVALID_ARG      # a full 64-bit seed is accepted
+
+
+def test_mfma_probe_validates_before_launch():
+    L = binding.lib()
+    null, fake = ctypes.c_void_p(0), ctypes.c_void_p(0x1000)
+    assert L.mosaic_mfma_probe_flops(10, 256) == 10 * 256 * 4 * 64 * 16 * 16 * 32 * 2
+    assert L.mosaic_mfma_probe_flops(-1, 256) == 0
+    assert L.mosaic_mfma_probe(null, fake, 10, 256, null) == binding.MOSAIC_ERR_INVALID_ARG
+    assert L.mosaic_mfma_probe(fake, null, 10, 256, null) == binding.MOSAIC_ERR_INVALID_ARG
+    assert L.mosaic_mfma_probe(fake, fake, 0, 256, null) == binding.MOSAIC_ERR_INVALID_ARG
+    assert L.mosaic_mfma_probe(fake, fake, 10, 0, null) == binding.MOSAIC_ERR_INVALID_ARG
+    assert L.mosaic_mfma_probe(fake, fake, 10, 70000, null) == binding.MOSAIC_ERR_INVALID_ARG
+    assert L.mosaic_mfma_probe(ctypes.c_void_p(0x1004), fake, 10, 256, null) == binding.MOSAIC_ERR_INVALID_ARG
