@@ -3,8 +3,8 @@
 
 One statement = the nk K-tiles of one vocabulary tile.  Per K-tile (step g) a wave issues 128
 v_mfma_f32_16x16x32_bf16 in two groups of 64 (k 0..31 and k 32..63 of the tile); after every second MFMA
-of a group's first half sits one of the 16 ds_read_b128 that fetch the next group's fragments, then one of
-up to 8 direct-to-LDS copies, so that nothing but MFMAs is ever waited on in steady state.  The steady-state body (1 <= g, g + 2 < total)
+of a group's first half sits one of the 16 ds_read_b128 that fetch the next group's fragments, and after every
+fourth one of the group's 8 direct-to-LDS copies, so that nothing but MFMAs is ever waited on in steady state.  The steady-state body (1 <= g, g + 2 < total)
 contains no branch at all -- a taken branch costs more than one 16-cycle MFMA -- and all slot / pointer
 book-keeping is s_cselect arithmetic; the first step and the last two run a guarded copy of the same schedule.
 """
@@ -110,45 +110,54 @@ def cond_plus(plus):
     e("s_cmp_lt_u32 vcc_lo, %[total]")
 
 
-def group(buf, rd=None, dma=None, cond=None, after=None):
+# Copy i of a tile goes out after MFMA COPY_POS[i] of its group: early in the group, so a copy has the longest
+# possible time to land before the sync that publishes it, and four MFMAs apart, so the 16 KiB a workgroup
+# requests per position never queue up behind the texture addresser (denser or later placement measured slower).
+COPY_POS = [1, 5, 9, 13, 17, 21, 25, 29]
+
+
+def group(buf, rd=None, dma=None, cond=None, after=None, pos=None):
     """64 MFMAs on fragment buffer `buf`.  rd = 16 ds_reads, one after each even MFMA 0..30.
-    dma = 8 copy sequences, one after each even MFMA 32..46, guarded by `cond` (emits scc); `after` runs
-    once the copies are out (state advance)."""
+    dma = 8 copy sequences, copy i after MFMA pos[i]; guarded by `cond` when given (then the guarded span is
+    pos[0]..pos[7]); `after` runs once the copies are out."""
     e("s_waitcnt lgkmcnt(0)")
     order = [(bi, bj) for bi in range(8) for bj in range(8)]
-    for k in range(32):
-        mfma(*order[k], buf)
-        if rd and k % 2 == 0:
-            e(rd[k // 2])
-    if dma and cond is None:
-        for k in range(32, 48):
+    if not dma:
+        for k in range(64):
             mfma(*order[k], buf)
-            if k % 2 == 0:
-                for x in dma[(k - 32) // 2]:
+            if rd and k % 2 == 0 and k < 32:
+                e(rd[k // 2])
+        return
+    lo, hi = pos[0], pos[-1]
+    for k in range(lo):
+        mfma(*order[k], buf)
+        if rd and k % 2 == 0 and k < 32:
+            e(rd[k // 2])
+    def span(with_dma):
+        for k in range(lo, hi + 1):
+            mfma(*order[k], buf)
+            if rd and k % 2 == 0 and k < 32:
+                e(rd[k // 2])
+            if with_dma and k in pos:
+                for x in dma[pos.index(k)]:
                     e(x)
-        if after:
+        if with_dma and after:
             after()
-    elif dma:
+    if cond is None:
+        span(True)
+    else:
         skip, join = label("nodma"), label("join")
         cond()
         e(f"s_cbranch_scc0 {skip}")
-        for k in range(32, 48):
-            mfma(*order[k], buf)
-            if k % 2 == 0:
-                for x in dma[(k - 32) // 2]:
-                    e(x)
-        if after:
-            after()
+        span(True)
         e(f"s_branch {join}")
         e(f"{skip}:")
-        for k in range(32, 48):
-            mfma(*order[k], buf)
+        span(False)
         e(f"{join}:")
-    else:
-        for k in range(32, 48):
-            mfma(*order[k], buf)
-    for k in range(48, 64):
+    for k in range(hi + 1, 64):
         mfma(*order[k], buf)
+        if rd and k % 2 == 0 and k < 32:
+            e(rd[k // 2])
 
 
 def step_end(top):
@@ -176,19 +185,19 @@ def build():
     cond_g_ge1_and(2)
     e(f"s_cbranch_scc0 {generic}")
     read_addr(1)
-    group(0, rd=reads(1), dma=[dma_w(i) for i in range(8)], after=advance_w)     # LM-head tile g+2
+    group(0, rd=reads(1), dma=[dma_w(i) for i in range(8)], after=advance_w, pos=COPY_POS)     # LM-head tile g+2
     e("s_waitcnt lgkmcnt(0)")
     e("s_waitcnt vmcnt(8)")       # all but the LM-head tile just issued
     e("s_barrier")
     rotate_read_slots()
     read_addr(0)
-    group(1, rd=reads(0), dma=[dma_h(i) for i in range(8)], after=advance_h)     # hidden tile g+2
+    group(1, rd=reads(0), dma=[dma_h(i) for i in range(8)], after=advance_h, pos=COPY_POS)     # hidden tile g+2
     step_end(top)
     e(f"s_branch {out}")
     # First step and the last two: same schedule with every part guarded.
     e(f"{generic}:")
     read_addr(1)
-    group(0, rd=reads(1), dma=[dma_w(i) for i in range(8)], cond=lambda: cond_g_ge1_and(2), after=advance_w)
+    group(0, rd=reads(1), dma=[dma_w(i) for i in range(8)], cond=lambda: cond_g_ge1_and(2), after=advance_w, pos=COPY_POS)
     nosync, stepend = label("nosync"), label("stepend")
     cond_plus(1)
     e(f"s_cbranch_scc0 {nosync}")
@@ -197,7 +206,7 @@ def build():
     e("s_barrier")
     rotate_read_slots()
     read_addr(0)
-    group(1, rd=reads(0), dma=[dma_h(i) for i in range(8)], cond=lambda: cond_plus(2), after=advance_h)
+    group(1, rd=reads(0), dma=[dma_h(i) for i in range(8)], cond=lambda: cond_plus(2), after=advance_h, pos=COPY_POS)
     e(f"s_branch {stepend}")
     e(f"{nosync}:")
     group(1)
