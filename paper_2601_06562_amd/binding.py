@@ -27,8 +27,24 @@ PLAN_GENERAL_KERNEL = 1   # plan.flags bit: force the general 8-wave kernel
 
 EXPORTS = (
     "mosaic_status_string", "mosaic_plan_workspace", "mosaic_compact_scratch_bytes", "mosaic_mask_compact",
-    "mosaic_masked_logits_reduce", "mosaic_sample_workspace_bytes", "mosaic_masked_logits_sample", "mosaic_unmask_topn", "mosaic_shift_indices", "mosaic_mfma_probe_flops", "mosaic_mfma_probe", "mosaic_version",
+    "mosaic_masked_logits_reduce", "mosaic_sample_workspace_bytes", "mosaic_masked_logits_sample",
+    "mosaic_unmask_topn", "mosaic_shift_indices", "mosaic_mfma_probe_flops", "mosaic_mfma_probe", "mosaic_version",
 )
+GRAPH_EXPORTS = (
+    "mosaic_graph_create", "mosaic_graph_destroy", "mosaic_graph_add_dim", "mosaic_graph_add_chunk_param",
+    "mosaic_graph_add_tensor", "mosaic_graph_add_op", "mosaic_graph_add_alias", "mosaic_graph_add_barrier",
+    "mosaic_graph_plan", "mosaic_graph_search",
+)
+
+
+class MosaicPlacement(ctypes.Structure):
+    _fields_ = [("tensor", ctypes.c_int32), ("iteration", ctypes.c_int32), ("first_step", ctypes.c_int32),
+                ("last_step", ctypes.c_int32), ("offset", ctypes.c_int64), ("bytes", ctypes.c_int64)]
+
+
+class MosaicPlanSummary(ctypes.Structure):
+    _fields_ = [("peak_bytes", ctypes.c_int64), ("num_blocks", ctypes.c_int64), ("num_steps", ctypes.c_int32),
+                ("peak_block", ctypes.c_int32), ("peak_op", ctypes.c_int32), ("peak_chunk", ctypes.c_int32)]
 
 
 class MosaicPlan(ctypes.Structure):
@@ -92,6 +108,26 @@ def lib():
         L.mosaic_mfma_probe_flops.argtypes = [i32, i32]
         L.mosaic_mfma_probe.restype = ctypes.c_int
         L.mosaic_mfma_probe.argtypes = [p, p, i32, i32, p]
+        L.mosaic_graph_create.restype = p
+        L.mosaic_graph_create.argtypes = []
+        L.mosaic_graph_destroy.restype = None
+        L.mosaic_graph_destroy.argtypes = [p]
+        L.mosaic_graph_add_dim.restype = ctypes.c_int
+        L.mosaic_graph_add_dim.argtypes = [p, ctypes.c_char_p]
+        L.mosaic_graph_add_chunk_param.restype = ctypes.c_int
+        L.mosaic_graph_add_chunk_param.argtypes = [p, ctypes.c_char_p, ctypes.c_int]
+        L.mosaic_graph_add_tensor.restype = ctypes.c_int
+        L.mosaic_graph_add_tensor.argtypes = [p, ctypes.c_char_p, i64, ctypes.c_int, ctypes.c_int, ctypes.c_int]
+        L.mosaic_graph_add_op.restype = ctypes.c_int
+        L.mosaic_graph_add_op.argtypes = [p, ctypes.c_char_p, p, ctypes.c_int, p, ctypes.c_int, ctypes.c_int]
+        L.mosaic_graph_add_alias.restype = ctypes.c_int
+        L.mosaic_graph_add_alias.argtypes = [p, ctypes.c_int, ctypes.c_int]
+        L.mosaic_graph_add_barrier.restype = ctypes.c_int
+        L.mosaic_graph_add_barrier.argtypes = [p, ctypes.c_int, ctypes.c_int]
+        L.mosaic_graph_plan.restype = ctypes.c_int
+        L.mosaic_graph_plan.argtypes = [p, p, ctypes.c_int, p, ctypes.c_int, p, i64, ctypes.POINTER(MosaicPlanSummary)]
+        L.mosaic_graph_search.restype = ctypes.c_int
+        L.mosaic_graph_search.argtypes = [p, p, ctypes.c_int, i64, p, ctypes.c_int, ctypes.POINTER(MosaicPlanSummary), p]
         _lib = L
     return _lib
 
@@ -212,6 +248,83 @@ def mosaic_mfma_probe(operands, sink, iters, num_wgs, stream=None) -> int:
     _check(lib().mosaic_mfma_probe(_dev_ptr(operands, "operands", torch.bfloat16), _dev_ptr(sink, "sink", torch.float32),
                                    int(iters), int(num_wgs), _stream_ptr(stream)), "mosaic_mfma_probe")
     return int(lib().mosaic_mfma_probe_flops(int(iters), int(num_wgs)))
+
+
+class GraphTemplate:
+    """The graph registrar behind the C ABI (mosaic_graph_*): same primitive names, marshalling only."""
+    NONE = -1
+
+    def __init__(self):
+        self._g = lib().mosaic_graph_create()
+        if not self._g:
+            raise MemoryError("mosaic_graph_create")
+        self.n_dims = 0
+        self.n_chunks = 0
+
+    def __del__(self):
+        g, self._g = getattr(self, "_g", None), None
+        if g:
+            lib().mosaic_graph_destroy(g)
+
+    def _id(self, rc, where):
+        if rc < 0:
+            raise MosaicError(rc, where)
+        return rc
+
+    def add_dim(self, name):
+        rc = self._id(lib().mosaic_graph_add_dim(self._g, name.encode()), "mosaic_graph_add_dim")
+        self.n_dims += 1
+        return rc
+
+    def add_chunk_param(self, name, dim):
+        rc = self._id(lib().mosaic_graph_add_chunk_param(self._g, name.encode(), dim), "mosaic_graph_add_chunk_param")
+        self.n_chunks += 1
+        return rc
+
+    def add_tensor(self, name, bytes_per_row, dim=-1, chunk=-1, persistent=False):
+        return self._id(lib().mosaic_graph_add_tensor(self._g, name.encode(), int(bytes_per_row), dim, chunk,
+                                                      int(bool(persistent))), "mosaic_graph_add_tensor")
+
+    def add_op(self, name, inputs, outputs, chunk=-1):
+        ins = (ctypes.c_int32 * max(len(inputs), 1))(*inputs)
+        outs = (ctypes.c_int32 * max(len(outputs), 1))(*outputs)
+        return self._id(lib().mosaic_graph_add_op(self._g, name.encode(), ins, len(inputs), outs, len(outputs), chunk),
+                        "mosaic_graph_add_op")
+
+    def add_alias(self, a, b):
+        _check(lib().mosaic_graph_add_alias(self._g, a, b), "mosaic_graph_add_alias")
+
+    def add_barrier(self, tensor, chunk):
+        _check(lib().mosaic_graph_add_barrier(self._g, tensor, chunk), "mosaic_graph_add_barrier")
+
+    def plan(self, dims, chunks, placements=True):
+        """(list of placement dicts in placement order, summary dict) for one instantiation."""
+        d = (ctypes.c_int64 * max(len(dims), 1))(*dims)
+        k = (ctypes.c_int32 * max(len(chunks), 1))(*chunks)
+        summary = MosaicPlanSummary()
+        _check(lib().mosaic_graph_plan(self._g, d, len(dims), k, len(chunks), None, 0, ctypes.byref(summary)),
+               "mosaic_graph_plan")
+        out = []
+        if placements and summary.num_blocks:
+            buf = (MosaicPlacement * summary.num_blocks)()
+            _check(lib().mosaic_graph_plan(self._g, d, len(dims), k, len(chunks), buf, summary.num_blocks,
+                                           ctypes.byref(summary)), "mosaic_graph_plan")
+            out = [dict(tensor=b.tensor, iteration=b.iteration, first_step=b.first_step, last_step=b.last_step,
+                        offset=b.offset, bytes=b.bytes) for b in buf]
+        return out, {f: getattr(summary, f) for f, _ in MosaicPlanSummary._fields_}
+
+    def search(self, dims, budget_bytes):
+        """(ok, chunk counts, summary dict, planning passes) of the bottleneck-driven search."""
+        d = (ctypes.c_int64 * max(len(dims), 1))(*dims)
+        k = (ctypes.c_int32 * max(self.n_chunks, 1))()
+        summary = MosaicPlanSummary()
+        evals = ctypes.c_int32(0)
+        rc = lib().mosaic_graph_search(self._g, d, len(dims), int(budget_bytes), k, self.n_chunks,
+                                       ctypes.byref(summary), ctypes.byref(evals))
+        if rc not in (MOSAIC_OK, MOSAIC_ERR_WORKSPACE_TOO_SMALL):
+            raise MosaicError(rc, "mosaic_graph_search")
+        return (rc == MOSAIC_OK, list(k)[:self.n_chunks],
+                {f: getattr(summary, f) for f, _ in MosaicPlanSummary._fields_}, evals.value)
 
 
 class MaskOnlyLogits:

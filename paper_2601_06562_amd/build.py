@@ -10,7 +10,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libmosaic.so")
 SOURCES = ["mosaic_api.hip", "mosaic_compact.hip", "mosaic_logits.hip", "mosaic_unmask.hip", "mosaic_probe.hip",
-           "mosaic_plan.cpp"]
+           "mosaic_plan.cpp", "mosaic_graph.cpp"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

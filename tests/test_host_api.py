@@ -17,6 +17,10 @@ def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "mosaic.h")).read()
     declared = set(re.findall(r"\b(mosaic_[a-z_]+)\s*\(", header))
     assert declared == set(binding.EXPORTS)
+    graph_header = open(os.path.join(ROOT, "include", "mosaic_graph.h")).read()
+    graph_declared = set(re.findall(r"\b(mosaic_graph_[a-z_]+)\s*\(", graph_header))
+    assert graph_declared == set(binding.GRAPH_EXPORTS)
+    declared |= graph_declared
     L = binding.lib()
     for name in declared:
         assert getattr(L, name) is not None
