@@ -204,6 +204,39 @@ int mosaic_shift_indices(const int32_t *idx, const int32_t *count, int64_t max_r
 int64_t mosaic_mfma_probe_flops(int32_t iters, int32_t num_wgs);
 int mosaic_mfma_probe(const void *operands, float *sink, int32_t iters, int32_t num_wgs, void *stream);
 
+/*
+ * Workspace on virtual memory (paper section 4.5, VMM-based allocator): reserve a large contiguous range of
+ * virtual addresses once (no memory is taken), then map physical pages behind its start up to the planned
+ * peak of each request; the pointer never changes, so it can be handed to the calls above as `workspace`
+ * (or sliced by the offsets of a mosaic_graph plan).
+ *   mosaic_vmm_create     reserves reserve_bytes (rounded up to the mapping granularity) on `device`, which
+ *                         must be the current device of the calling thread for every later call on the object.
+ *                         UNSUPPORTED_SHAPE if the device has no virtual memory management.
+ *   mosaic_vmm_resize     makes exactly `bytes`, rounded up to the granularity, of the range usable.  A call
+ *                         that changes the rounded size waits for the device to be idle (hipDeviceSynchronize
+ *                         -- the only call of this library that does), drops the old mapping and maps new
+ *                         pages at the same address: the contents do NOT survive it.  A call that does not
+ *                         change it does nothing.  WORKSPACE_TOO_SMALL if bytes exceeds the reservation (nothing
+ *                         changes); HIP if the driver refuses, e.g. out of memory (the range is then left with
+ *                         nothing mapped: committed_bytes() == 0).
+ *   mosaic_vmm_ptr        device pointer to the start of the range (granularity-aligned); only the first
+ *                         mosaic_vmm_committed_bytes() bytes may be touched -- beyond them is unmapped
+ *                         address space and an access faults.
+ *   mosaic_vmm_destroy    waits for the device, unmaps, releases and frees the reservation; accepts NULL.
+ * The object is owned by the caller and is not thread-safe.
+ */
+typedef struct mosaic_vmm mosaic_vmm;
+int mosaic_vmm_create(int device, int64_t reserve_bytes, mosaic_vmm **out);
+int mosaic_vmm_resize(mosaic_vmm *v, int64_t bytes);
+void *mosaic_vmm_ptr(const mosaic_vmm *v);
+int64_t mosaic_vmm_committed_bytes(const mosaic_vmm *v);
+int64_t mosaic_vmm_reserved_bytes(const mosaic_vmm *v);
+int64_t mosaic_vmm_granularity(const mosaic_vmm *v);
+/* Name of the driver call behind the most recent MOSAIC_ERR_HIP of mosaic_vmm_resize ("" if none) and, if
+ * hip_error is not NULL, its hipError_t value.  Static storage. */
+const char *mosaic_vmm_last_error(const mosaic_vmm *v, int *hip_error);
+int mosaic_vmm_destroy(mosaic_vmm *v);
+
 /* Library version, "major.minor" as major*1000 + minor. */
 int mosaic_version(void);
 

@@ -29,6 +29,8 @@ EXPORTS = (
     "mosaic_status_string", "mosaic_plan_workspace", "mosaic_compact_scratch_bytes", "mosaic_mask_compact",
     "mosaic_masked_logits_reduce", "mosaic_sample_workspace_bytes", "mosaic_masked_logits_sample",
     "mosaic_unmask_topn", "mosaic_shift_indices", "mosaic_mfma_probe_flops", "mosaic_mfma_probe", "mosaic_version",
+    "mosaic_vmm_create", "mosaic_vmm_resize", "mosaic_vmm_ptr", "mosaic_vmm_committed_bytes",
+    "mosaic_vmm_reserved_bytes", "mosaic_vmm_granularity", "mosaic_vmm_last_error", "mosaic_vmm_destroy",
 )
 GRAPH_EXPORTS = (
     "mosaic_graph_create", "mosaic_graph_destroy", "mosaic_graph_add_dim", "mosaic_graph_add_chunk_param",
@@ -108,6 +110,19 @@ def lib():
         L.mosaic_mfma_probe_flops.argtypes = [i32, i32]
         L.mosaic_mfma_probe.restype = ctypes.c_int
         L.mosaic_mfma_probe.argtypes = [p, p, i32, i32, p]
+        L.mosaic_vmm_create.restype = ctypes.c_int
+        L.mosaic_vmm_create.argtypes = [ctypes.c_int, i64, ctypes.POINTER(ctypes.c_void_p)]
+        L.mosaic_vmm_resize.restype = ctypes.c_int
+        L.mosaic_vmm_resize.argtypes = [p, i64]
+        L.mosaic_vmm_ptr.restype = p
+        L.mosaic_vmm_ptr.argtypes = [p]
+        for name in ("mosaic_vmm_committed_bytes", "mosaic_vmm_reserved_bytes", "mosaic_vmm_granularity"):
+            getattr(L, name).restype = i64
+            getattr(L, name).argtypes = [p]
+        L.mosaic_vmm_last_error.restype = ctypes.c_char_p
+        L.mosaic_vmm_last_error.argtypes = [p, ctypes.POINTER(ctypes.c_int)]
+        L.mosaic_vmm_destroy.restype = ctypes.c_int
+        L.mosaic_vmm_destroy.argtypes = [p]
         L.mosaic_graph_create.restype = p
         L.mosaic_graph_create.argtypes = []
         L.mosaic_graph_destroy.restype = None
@@ -157,6 +172,15 @@ def _dev_ptr(t, name, dtype=None):
     return ctypes.c_void_p(t.data_ptr())
 
 
+def _workspace_args(workspace):
+    """(pointer, bytes) of a workspace given as a device tensor or as a VmmWorkspace (its mapped prefix)."""
+    if workspace is None:
+        return ctypes.c_void_p(0), 0
+    if isinstance(workspace, VmmWorkspace):
+        return ctypes.c_void_p(workspace.ptr), workspace.committed_bytes
+    return _dev_ptr(workspace, "workspace"), workspace.numel() * workspace.element_size()
+
+
 def mosaic_plan_workspace(T, max_rows, d, V, budget_bytes=0, num_cus=0) -> MosaicPlan:
     plan = MosaicPlan()
     _check(lib().mosaic_plan_workspace(T, max_rows, d, V, budget_bytes, num_cus, ctypes.byref(plan)),
@@ -194,8 +218,8 @@ def mosaic_masked_logits_reduce(hidden, w, idx, count, max_rows, out_token, out_
         _dev_ptr(hidden, "hidden", torch.bfloat16), T, d, ld_h, _dev_ptr(w, "w", torch.bfloat16), V,
         _dev_ptr(idx, "idx", torch.int32), _dev_ptr(count, "count", torch.int32), max_rows,
         _dev_ptr(out_token, "out_token", torch.int32), _dev_ptr(out_conf, "out_conf", torch.float32),
-        _dev_ptr(out_lse, "out_lse", torch.float32), ctypes.byref(plan), _dev_ptr(workspace, "workspace"),
-        workspace.numel() * workspace.element_size() if workspace is not None else 0, _stream_ptr(stream)),
+        _dev_ptr(out_lse, "out_lse", torch.float32), ctypes.byref(plan), *_workspace_args(workspace),
+        _stream_ptr(stream)),
         "mosaic_masked_logits_reduce")
 
 
@@ -219,8 +243,8 @@ def mosaic_masked_logits_sample(hidden, w, idx, count, max_rows, temperature, se
         _dev_ptr(idx, "idx", torch.int32), _dev_ptr(count, "count", torch.int32), max_rows,
         float(temperature), int(seed) & 0xFFFFFFFFFFFFFFFF,
         _dev_ptr(out_token, "out_token", torch.int32), _dev_ptr(out_conf, "out_conf", torch.float32),
-        _dev_ptr(out_lse, "out_lse", torch.float32), ctypes.byref(plan), _dev_ptr(workspace, "workspace"),
-        workspace.numel() * workspace.element_size() if workspace is not None else 0, _stream_ptr(stream)),
+        _dev_ptr(out_lse, "out_lse", torch.float32), ctypes.byref(plan), *_workspace_args(workspace),
+        _stream_ptr(stream)),
         "mosaic_masked_logits_sample")
 
 
@@ -248,6 +272,50 @@ def mosaic_mfma_probe(operands, sink, iters, num_wgs, stream=None) -> int:
     _check(lib().mosaic_mfma_probe(_dev_ptr(operands, "operands", torch.bfloat16), _dev_ptr(sink, "sink", torch.float32),
                                    int(iters), int(num_wgs), _stream_ptr(stream)), "mosaic_mfma_probe")
     return int(lib().mosaic_mfma_probe_flops(int(iters), int(num_wgs)))
+
+
+class VmmWorkspace:
+    """A reserved virtual range whose mapped prefix follows the planned peak (mosaic_vmm_*)."""
+
+    def __init__(self, reserve_bytes, device=0):
+        h = ctypes.c_void_p()
+        _check(lib().mosaic_vmm_create(int(device), int(reserve_bytes), ctypes.byref(h)), "mosaic_vmm_create")
+        self._h = h
+
+    def resize(self, nbytes):
+        rc = lib().mosaic_vmm_resize(self._h, int(nbytes))
+        if rc == MOSAIC_ERR_HIP:
+            code = ctypes.c_int(0)
+            call = lib().mosaic_vmm_last_error(self._h, ctypes.byref(code)).decode()
+            raise MosaicError(rc, f"mosaic_vmm_resize [{call} -> hipError {code.value}]")
+        _check(rc, "mosaic_vmm_resize")
+
+    @property
+    def ptr(self) -> int:
+        return int(lib().mosaic_vmm_ptr(self._h) or 0)
+
+    @property
+    def committed_bytes(self) -> int:
+        return int(lib().mosaic_vmm_committed_bytes(self._h))
+
+    @property
+    def reserved_bytes(self) -> int:
+        return int(lib().mosaic_vmm_reserved_bytes(self._h))
+
+    @property
+    def granularity(self) -> int:
+        return int(lib().mosaic_vmm_granularity(self._h))
+
+    def close(self):
+        h, self._h = getattr(self, "_h", None), None
+        if h:
+            _check(lib().mosaic_vmm_destroy(h), "mosaic_vmm_destroy")
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 class GraphTemplate:

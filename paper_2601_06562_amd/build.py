@@ -9,7 +9,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libmosaic.so")
-SOURCES = ["mosaic_api.hip", "mosaic_compact.hip", "mosaic_logits.hip", "mosaic_unmask.hip", "mosaic_probe.hip",
+SOURCES = ["mosaic_api.hip", "mosaic_compact.hip", "mosaic_logits.hip", "mosaic_unmask.hip", "mosaic_probe.hip", "mosaic_vmm.hip",
            "mosaic_plan.cpp", "mosaic_graph.cpp"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -182,3 +182,16 @@ def test_mfma_probe_validates_before_launch():
     assert L.mosaic_mfma_probe(fake, fake, 10, 0, null) == binding.MOSAIC_ERR_INVALID_ARG
     assert L.mosaic_mfma_probe(fake, fake, 10, 70000, null) == binding.MOSAIC_ERR_INVALID_ARG
     assert L.mosaic_mfma_probe(ctypes.c_void_p(0x1004), fake, 10, 256, null) == binding.MOSAIC_ERR_INVALID_ARG
+
+
+def test_vmm_entry_points_validate_their_arguments():
+    L = binding.lib()
+    h = ctypes.c_void_p()
+    assert L.mosaic_vmm_create(0, 1 << 20, None) == binding.MOSAIC_ERR_INVALID_ARG
+    assert L.mosaic_vmm_create(-1, 1 << 20, ctypes.byref(h)) == binding.MOSAIC_ERR_INVALID_ARG and not h
+    assert L.mosaic_vmm_create(0, 0, ctypes.byref(h)) == binding.MOSAIC_ERR_INVALID_ARG and not h
+    assert L.mosaic_vmm_resize(None, 10) == binding.MOSAIC_ERR_INVALID_ARG
+    assert L.mosaic_vmm_ptr(None) is None
+    assert L.mosaic_vmm_committed_bytes(None) == 0 and L.mosaic_vmm_reserved_bytes(None) == 0
+    assert L.mosaic_vmm_granularity(None) == 0
+    assert L.mosaic_vmm_destroy(None) == binding.MOSAIC_OK
