@@ -28,6 +28,10 @@ def main():
     ap.add_argument("--budget-bytes", type=int, default=0, help="workspace budget for the chunk-size selector")
     ap.add_argument("--cpu-rows", type=int, default=4096, help="rows of the workload the CPU oracle is timed on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="time replays of one captured HIP graph of the step instead of eager launches (the count "
+                         "stays on the device, so the step is capturable as it is); per-kernel events are then "
+                         "taken around the whole step")
     ap.add_argument("--temperature", type=float, default=0.0,
                     help="> 0 times the Gumbel-max sampling variant of the fused kernel instead of the greedy one "
                          "(not the headline configuration)")
@@ -80,6 +84,30 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    if args.graph:
+        eager_step = step
+        side = torch.cuda.Stream()
+        side.wait_stream(stream)
+        with torch.cuda.stream(side):
+            stream = side
+            eager_step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            stream = torch.cuda.current_stream()
+            eager_step()
+        stream = torch.cuda.current_stream()
+
+        def step(ev=None):
+            if ev is not None:
+                ev[0].record(stream)
+            graph.replay()
+            if ev is not None:
+                ev[1].record(stream)
+        for _ in range(args.warmup):
+            step()
+        torch.cuda.synchronize()
     events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
     t0 = time.perf_counter()
     for k in range(args.steps):
@@ -131,7 +159,8 @@ def main():
         "config": {"workload": args.workload, "T": wl.T, "d": wl.d, "V": wl.V, "masked_rows": M,
                    "num_chunks": op.plan.num_chunks, "rows_per_chunk": op.plan.rows_per_chunk,
                    "vocab_splits": op.plan.vocab_splits, "grid": op.plan.grid,
-                   "decode": "greedy" if args.temperature <= 0 else f"gumbel-max tau={args.temperature}"},
+                   "decode": "greedy" if args.temperature <= 0 else f"gumbel-max tau={args.temperature}",
+                   "launch": "hip-graph replay" if args.graph else "eager"},
         "tflops": flop / sec_per_step / 1e12,
         "pct_bf16_mfma_peak": 100.0 * flop / sec_per_step / 1e12 / PEAK_BF16_TFLOPS,
         "peak_workspace_bytes": op.workspace_bytes,
