@@ -50,7 +50,7 @@ const char *mosaic_status_string(int status);
 #define MOSAIC_ROW_TILE 256
 #define MOSAIC_VOCAB_TILE 256
 #define MOSAIC_K_TILE 64
-#define MOSAIC_MAX_VOCAB_SPLITS 64
+#define MOSAIC_MAX_VOCAB_SPLITS 256
 
 /* Result of the chunk-size selector.  All fields are filled by mosaic_plan_workspace;
  * callers may read them and may set `flags`, nothing else. */

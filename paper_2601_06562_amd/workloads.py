@@ -43,6 +43,9 @@ SPECS = {
     "long_semi_ar": (3, 1, 32768, 4096, 126464),
     "dream_late_step": (4, 1, 65536, 3584, 152064),
     "batched_mixed": (5, 8, 16384, 4096, 126464),
+    # beyond the five benchmark configurations: the last steps of a block-wise decode, when few positions of the
+    # block under generation are still masked (the regime where the LM head is read once for very few rows)
+    "llada_block_tail": (6, 1, 4096, 4096, 126464),
 }
 BATCHED_RATIOS = (0.02, 0.05, 0.1, 0.25, 0.5, 0.75, 0.9, 1.0)
 
@@ -97,6 +100,10 @@ def make(name: str, device="cpu", scale_down: int = 1) -> Workload:
         mask[prompt:] = _bernoulli(T - prompt, 0.5, gen, device)
     elif name == "dream_late_step":
         mask = _bernoulli(T, 0.1, gen, device)
+    elif name == "llada_block_tail":
+        mask = torch.zeros(T, dtype=torch.uint8, device=device)
+        block = min(512, T // 2)
+        mask[T - block:] = _bernoulli(block, 0.4, gen, device)     # ~200 masked positions in the last block
     elif name == "batched_mixed":
         mask = torch.cat([_bernoulli(L, r, gen, device) for r in BATCHED_RATIOS])
     else:  # pragma: no cover

@@ -71,6 +71,9 @@ SMALL = [
     (1000, 320, 1280, 0.5),
     (130, 512, 2560, 1.0),
     (2100, 64, 4096, 0.9),
+    # few rows against a wide vocabulary: one row tile spread over 128+ vocabulary splits
+    (300, 256, 65536, 0.5),
+    (600, 128, 50176, 0.6),
 ]
 
 

@@ -80,6 +80,7 @@ SHAPES = [
     (1000, 320, 1280, 0.5),
     (130, 512, 2560, 1.0),
     (2100, 64, 4096, 0.9),
+    (300, 256, 65536, 0.5),      # one row tile, 128 vocabulary splits
 ]
 
 

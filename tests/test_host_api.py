@@ -48,7 +48,7 @@ def test_selector_unbounded_is_one_chunk(rows):
     plan = binding.mosaic_plan_workspace(131072, rows, 4096, 126464, 0)
     assert plan.num_chunks == 1 and plan.rows_per_chunk >= rows and plan.rows_per_chunk % 256 == 0
     assert plan.workspace_bytes == workspace(plan.rows_per_chunk, plan.vocab_splits)
-    assert 1 <= plan.vocab_splits <= 64 and 1 <= plan.grid <= 256
+    assert 1 <= plan.vocab_splits <= 256 and 1 <= plan.grid <= 256
 
 
 @pytest.mark.parametrize("rows", [300, 4096, 5000, 58491])
