@@ -792,35 +792,55 @@ __global__ __launch_bounds__(256) void masked_logits_kernel_w4(const KernelParam
   }
 }
 
-// Merge the S partial triples of every row in ascending split order and emit the outputs.
+// Merge the S partial results of every row and emit the outputs.  A block handles 16 rows; its 16 thread groups
+// each fold the splits g, g+16, g+32, ... in ascending order and thread group 0 then folds the 16 group results in
+// ascending order, so the order is a function of S alone (run-to-run and chunking-independent results) while a
+// row's chain of dependent loads is S/16 long instead of S (with one row tile spread over ~250 splits the
+// sequential merge took a third of the step).
+constexpr int kCombineRows = 16;
 __global__ __launch_bounds__(256) void combine_kernel(const KernelParams p) {
+  __shared__ float sh_m[16][kCombineRows], sh_s[16][kCombineRows], sh_ym[16][kCombineRows], sh_xa[16][kCombineRows];
+  __shared__ int sh_i[16][kCombineRows];
   int total = *p.count;
   if (total > p.max_rows) total = p.max_rows;
   int rows = total - p.row0;
   if (rows > p.chunk_rows) rows = p.chunk_rows;
-  const int r = blockIdx.x * 256 + threadIdx.x;
-  if (r >= rows) return;
-  float m = kNeg, s = 0.f;
+  const int lr = threadIdx.x & (kCombineRows - 1), g = threadIdx.x >> 4;
+  const int r = blockIdx.x * kCombineRows + lr;
+  const bool valid = r < rows;
+  const bool sample = p.tau > 0.f;   // sampling: the token is the arg-max of the perturbed scores
+  float m = kNeg, s = 0.f, ym = kNeg, xa = 0.f;
   int i = INT_MAX;
-  if (p.tau > 0.f) {   // sampling: the token is the arg-max of the perturbed scores, conf its soft-max probability
-    float ym = kNeg, xa = 0.f;
-    for (int sp = 0; sp < p.splits; ++sp) {
+  if (valid) {
+    for (int sp = g; sp < p.splits; sp += 16) {
       const int64_t slot = (int64_t)sp * p.c_pad + r;
-      merge_ms(m, s, p.part_m[slot], p.part_s[slot]);
-      merge_pick(ym, xa, i, p.part_ym[slot], p.part_xa[slot], p.part_i[slot]);
+      if (sample) {
+        merge_ms(m, s, p.part_m[slot], p.part_s[slot]);
+        merge_pick(ym, xa, i, p.part_ym[slot], p.part_xa[slot], p.part_i[slot]);
+      } else {
+        merge_triple(m, s, i, p.part_m[slot], p.part_s[slot], p.part_i[slot]);
+      }
     }
-    p.out_token[p.row0 + r] = i;
-    p.out_lse[p.row0 + r] = m + __builtin_amdgcn_logf(s) * kLn2;
-    p.out_conf[p.row0 + r] = __builtin_amdgcn_exp2f((xa - m) * kLog2e) / s;
-    return;
   }
-  for (int sp = 0; sp < p.splits; ++sp) {
-    const int64_t slot = (int64_t)sp * p.c_pad + r;
-    merge_triple(m, s, i, p.part_m[slot], p.part_s[slot], p.part_i[slot]);
+  sh_m[g][lr] = m;
+  sh_s[g][lr] = s;
+  sh_i[g][lr] = i;
+  sh_ym[g][lr] = ym;
+  sh_xa[g][lr] = xa;
+  __syncthreads();
+  if (g != 0 || !valid) return;
+  const int groups = p.splits < 16 ? p.splits : 16;   // groups beyond S hold the neutral element
+  for (int gg = 1; gg < groups; ++gg) {
+    if (sample) {
+      merge_ms(m, s, sh_m[gg][lr], sh_s[gg][lr]);
+      merge_pick(ym, xa, i, sh_ym[gg][lr], sh_xa[gg][lr], sh_i[gg][lr]);
+    } else {
+      merge_triple(m, s, i, sh_m[gg][lr], sh_s[gg][lr], sh_i[gg][lr]);
+    }
   }
   p.out_token[p.row0 + r] = i;
   p.out_lse[p.row0 + r] = m + __builtin_amdgcn_logf(s) * kLn2;
-  p.out_conf[p.row0 + r] = 1.0f / s;
+  p.out_conf[p.row0 + r] = sample ? __builtin_amdgcn_exp2f((xa - m) * kLog2e) / s : 1.0f / s;
 }
 
 int launch_masked_logits(const LogitsArgs& a, const mosaic_plan& plan, hipStream_t stream) {
@@ -873,7 +893,7 @@ int launch_masked_logits(const LogitsArgs& a, const mosaic_plan& plan, hipStream
       hipLaunchKernelGGL((masked_logits_kernel<3, 2, true>), dim3((unsigned)grid), dim3(kThreads), 0, stream, p);
     else
       hipLaunchKernelGGL((masked_logits_kernel<3, 2, false>), dim3((unsigned)grid), dim3(kThreads), 0, stream, p);
-    hipLaunchKernelGGL(combine_kernel, dim3((unsigned)((cap + 255) / 256)), dim3(256), 0, stream, p);
+    hipLaunchKernelGGL(combine_kernel, dim3((unsigned)((cap + kCombineRows - 1) / kCombineRows)), dim3(256), 0, stream, p);
   }
   return hipGetLastError() == hipSuccess ? 0 : -1;
 }

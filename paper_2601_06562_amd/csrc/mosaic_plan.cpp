@@ -28,7 +28,7 @@ int32_t choose_vocab_splits(int64_t row_tiles, int64_t vocab_tiles, int32_t num_
     const int64_t units = row_tiles * s;
     const int64_t rounds = (units + num_cus - 1) / num_cus;
     const int64_t longest = (vocab_tiles + s - 1) / s;
-    const int64_t cost = rounds * (4 * longest + 1);  // quarter-tile units: 1/4 tile of overhead per unit
+    const int64_t cost = rounds * (2 * longest + 1);  // half-tile units: pipeline fill, merge and partials of a unit ~ 1/2 tile
     if (best_cost < 0 || cost < best_cost) {
       best_cost = cost;
       best = (int32_t)s;
