@@ -69,3 +69,28 @@ def test_full_size_workload(name):
         want2 = oracle_rows(wl.hidden, w_bits, unmasked.cpu().numpy())
         check_against_oracle(dict(tok=out2["tok"][:8], conf=out2["conf"][:8], lse=out2["lse"][:8]), want2,
                              what=name + " unmasked rows")
+
+
+def test_hidden_tensor_beyond_4_gib_uses_64_bit_row_offsets():
+    """A hidden tensor larger than 4 GiB: the masked rows sit past the 4 GiB mark, where a 32-bit byte offset wraps.
+    (Such shapes are routed to the general kernel, which addresses rows with 64-bit pointers.)"""
+    import oracle
+    T, d, V = (1 << 19) + 4096, 4096, 1024                  # 4.03 GiB of bf16 hidden states
+    print(f"beyond-4GiB hidden: T={T} d={d} V={V}", flush=True)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(workloads.BASE_SEED + 77)
+    hidden = workloads._normal_bf16(T, d, 1.0, gen, torch.device(DEV))
+    w = workloads._normal_bf16(V, d, d ** -0.5, gen, torch.device(DEV))
+    mask = torch.zeros(T, dtype=torch.uint8, device=DEV)
+    pos = torch.cat([torch.arange(5, 40, 7), torch.arange((1 << 19) - 3, (1 << 19) + 300, 1), torch.tensor([T - 1])])
+    mask[pos.to(DEV)] = 1
+    assert int(pos.max()) * d * 2 > (1 << 32)
+    out = run_hip(hidden, w, mask, max_rows=int(pos.numel()))
+    M = out["M"]
+    assert M == pos.numel() and np.array_equal(out["idx"][:M], np.sort(pos.numpy()).astype(np.int32))
+    want = oracle_rows(hidden, workloads.bf16_bits(w), out["idx"][:M])
+    stats = check_against_oracle(dict(tok=out["tok"][:M], conf=out["conf"][:M], lse=out["lse"][:M]), want,
+                                 what="beyond 4 GiB")
+    print(stats, flush=True)
+    del hidden
+    torch.cuda.empty_cache()
