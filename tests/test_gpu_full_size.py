@@ -94,3 +94,29 @@ def test_hidden_tensor_beyond_4_gib_uses_64_bit_row_offsets():
     print(stats, flush=True)
     del hidden
     torch.cuda.empty_cache()
+
+
+def test_hidden_tensor_between_2_and_4_gib_on_the_fast_path():
+    """Rows whose 32-bit byte offset has its top bit set: the 4-wave kernel adds the per-lane offset to a 64-bit
+    base as an unsigned value (the documented behaviour of the scalar-base addressing form), so a hidden tensor
+    of up to 4 GiB stays on the fast path."""
+    T, d, V = 400000, 4096, 1024                            # 3.05 GiB of bf16 hidden states, V a multiple of 256
+    print(f"2-4 GiB hidden: T={T} d={d} V={V}", flush=True)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(workloads.BASE_SEED + 78)
+    hidden = workloads._normal_bf16(T, d, 1.0, gen, torch.device(DEV))
+    w = workloads._normal_bf16(V, d, d ** -0.5, gen, torch.device(DEV))
+    mask = torch.zeros(T, dtype=torch.uint8, device=DEV)
+    pos = torch.cat([torch.arange(3, 30, 9), torch.arange((1 << 18) - 2, (1 << 18) + 400, 1), torch.tensor([T - 1])])
+    mask[pos.to(DEV)] = 1
+    assert (1 << 31) < int(pos.max()) * d * 2 < (1 << 32)
+    out = run_hip(hidden, w, mask, max_rows=int(pos.numel()))
+    assert not (out["op"].plan.flags & 1)
+    M = out["M"]
+    assert M == pos.numel()
+    want = oracle_rows(hidden, workloads.bf16_bits(w), out["idx"][:M])
+    stats = check_against_oracle(dict(tok=out["tok"][:M], conf=out["conf"][:M], lse=out["lse"][:M]), want,
+                                 what="2-4 GiB")
+    print(stats, flush=True)
+    del hidden
+    torch.cuda.empty_cache()
