@@ -124,7 +124,8 @@ int mosaic_mask_compact(const uint8_t *mask, int64_t T, int32_t *out_idx, int32_
  *   max_rows   the bound the plan was made for
  *   out_*      dev, max_rows entries each; entries >= *count are left untouched
  *   plan       host pointer, from mosaic_plan_workspace with the same T, max_rows, d, V
- *   workspace  dev, >= plan->workspace_bytes, 16-byte aligned; contents are scratch
+ *   workspace  dev, >= plan->workspace_bytes, 16-byte aligned; contents are scratch.  Calls that may run
+ *              concurrently (different streams) need workspaces of their own
  * max_rows == 0 or V == 0 enqueue nothing.  Inputs must be finite; a NaN or Inf in a
  * row gives unspecified values for that row only.  Errors: INVALID_ARG,
  * UNSUPPORTED_SHAPE (d % MOSAIC_K_TILE, ld_h, T >= 2^31, V >= 2^31 - 256),
