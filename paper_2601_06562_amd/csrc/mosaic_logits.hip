@@ -15,10 +15,15 @@
 // so the reduction over the vocabulary is almost entirely in-register; the cross-lane steps and the
 // cross-wave step happen once per work unit, not per tile.
 //
-// Work decomposition.  A unit is (row tile of 256 masked tokens, vocabulary split); a workgroup of
-// 8 waves walks the 256-wide vocabulary tiles of its split, carrying the running triple in registers,
-// and writes one partial triple per row at the end.  A second tiny kernel merges the S partials per
-// row in fixed order (deterministic) and emits token, confidence and log-sum-exp.
+// Work decomposition.  A unit is (row tile of 256 masked tokens, vocabulary split); a workgroup (4 waves
+// in the hand-scheduled kernel, 8 in the general one) walks the 256-wide vocabulary tiles of its split,
+// carrying the running triple in registers, and writes one partial triple per row at the end.  A second
+// tiny kernel merges the S partials per row in an order fixed by S (deterministic) and emits token,
+// confidence and log-sum-exp.
+//
+// Sampling.  The SAMPLE instantiations of both kernels draw the token by the Gumbel-max form of categorical
+// sampling at temperature tau (paper section 2.1 leaves the sampler open): arg-max of x + tau*g with g from a
+// Philox4x32-10 stream keyed by (seed, position, vocabulary id), next to the unperturbed max / sum-exp.
 //
 // Data movement.  Global->LDS copies use the direct-to-LDS 16-byte loads of gfx950; both tiles are
 // K-contiguous ([256 rows][64 k] bf16 = 128 B per row, i.e. whole 128-byte lines per request) and
