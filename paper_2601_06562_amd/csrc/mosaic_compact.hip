@@ -2,8 +2,9 @@
 //
 // Paper section 4.2: the gather-GEMM kernel is handed "mask indices (identifying masked
 // tokens)"; the paper leaves their production to the framework.  Here it is an explicit
-// exclusive prefix sum over (mask[t] != 0) followed by a scatter, in three small launches
-// that never touch the host: per-block counts, a scan of those counts, the scatter.
+// exclusive prefix sum over (mask[t] != 0) followed by a scatter that never touches the host:
+// one single-block launch for up to 65536 positions (a denoising step of one long sequence),
+// otherwise three small launches (per-block counts, a scan of those counts, the scatter).
 // Integer work only; the result is unique (stable order), so it is bit-exact by construction.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -39,8 +40,10 @@ __device__ __forceinline__ uint32_t load_flags(const uint8_t* __restrict__ mask,
   return bits;
 }
 
-// Inclusive scan of one int per thread over a 256-thread block: wave shuffles, then 4 wave totals.
-__device__ __forceinline__ int block_inclusive_scan(int v, int* wave_totals /* LDS, 4 ints */, int* block_total) {
+// Inclusive scan of one int per thread over a block of THREADS threads: wave shuffles, then the wave totals.
+template <int THREADS = kCompactThreads>
+__device__ __forceinline__ int block_inclusive_scan(int v, int* wave_totals /* LDS, THREADS/64 ints */,
+                                                    int* block_total) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 #pragma unroll
   for (int off = 1; off < 64; off <<= 1) {
@@ -51,7 +54,7 @@ __device__ __forceinline__ int block_inclusive_scan(int v, int* wave_totals /* L
   __syncthreads();
   int before = 0, total = 0;
 #pragma unroll
-  for (int w = 0; w < kCompactThreads / 64; ++w) {
+  for (int w = 0; w < THREADS / 64; ++w) {
     const int t = wave_totals[w];
     if (w < wave) before += t;
     total += t;
@@ -116,8 +119,40 @@ __global__ __launch_bounds__(kCompactThreads) void compact_scatter_kernel(const 
   }
 }
 
+// Everything in one block, for masks of up to kSingleMax positions: passes of 16384 positions, the running
+// offset carried from pass to pass.  One launch instead of three where launches are all the cost.
+constexpr int kSingleThreads = 1024;
+constexpr int64_t kSingleMax = 65536;
+__global__ __launch_bounds__(kSingleThreads) void compact_single_kernel(const uint8_t* __restrict__ mask, int64_t T,
+                                                                        int32_t* __restrict__ out_idx,
+                                                                        int32_t* __restrict__ out_count) {
+  __shared__ int wave_totals[kSingleThreads / 64];
+  const bool aligned16 = (reinterpret_cast<uintptr_t>(mask) & 15u) == 0;
+  int running = 0;
+  for (int64_t pass0 = 0; pass0 < T; pass0 += (int64_t)kSingleThreads * kBytesPerThread) {
+    const int64_t base = pass0 + (int64_t)threadIdx.x * kBytesPerThread;
+    uint32_t bits = load_flags(mask, base, T, aligned16);
+    const int c = __popc(bits);
+    int total;
+    const int incl = block_inclusive_scan<kSingleThreads>(c, wave_totals, &total);
+    int out = running + incl - c;
+    while (bits) {
+      const int j = __ffs(bits) - 1;
+      bits &= bits - 1;
+      out_idx[out++] = (int32_t)(base + j);
+    }
+    running += total;
+    __syncthreads();   // the wave totals are rewritten by the next pass
+  }
+  if (threadIdx.x == 0) *out_count = running;
+}
+
 int launch_compact(const uint8_t* mask, int64_t T, int32_t* out_idx, int32_t* out_count, int32_t* block_counts,
                    hipStream_t stream) {
+  if (T <= kSingleMax) {
+    hipLaunchKernelGGL(compact_single_kernel, dim3(1), dim3(kSingleThreads), 0, stream, mask, T, out_idx, out_count);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+  }
   const int64_t nb = compact_num_blocks(T);
   if (nb > 0) {
     hipLaunchKernelGGL(compact_count_kernel, dim3((unsigned)nb), dim3(kCompactThreads), 0, stream, mask, T,

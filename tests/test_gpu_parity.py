@@ -19,7 +19,8 @@ def bf16(a):
 
 
 # ------------------------------------------------------------------ a1: compaction, bit-exact
-@pytest.mark.parametrize("T", [0, 1, 15, 16, 17, 63, 64, 65, 4095, 4096, 4097, 8192, 12345, 131072, 1000003])
+@pytest.mark.parametrize("T", [0, 1, 15, 16, 17, 63, 64, 65, 4095, 4096, 4097, 8192, 12345, 16384, 16385, 40000, 65535, 65536,
+                               65537, 131072, 1000003])
 @pytest.mark.parametrize("p", [0.0, 0.03, 0.5, 1.0])
 def test_compaction_bit_exact(T, p):
     print(f"compaction T={T} p={p}", flush=True)
