@@ -41,6 +41,8 @@ def _load():
         lib.oracle_mask_select.argtypes = [p, i64, p]
         lib.oracle_row_logits.restype = None
         lib.oracle_row_logits.argtypes = [p, p, i32, i32, p]
+        lib.oracle_row_logits_f32seq.restype = None
+        lib.oracle_row_logits_f32seq.argtypes = [p, p, i32, i32, p]
         lib.oracle_row_reduce.restype = None
         lib.oracle_row_reduce.argtypes = [p, i32, p, p, p, p, p]
         lib.oracle_positions.restype = ctypes.c_int
@@ -108,6 +110,16 @@ def row_logits(h_row: np.ndarray, W: np.ndarray) -> np.ndarray:
     assert h_row.shape == (d,)
     x = np.empty(V, dtype=np.float32)
     _load().oracle_row_logits(_ptr(h_row), _ptr(W), d, V, _ptr(x))
+    return x
+
+
+def row_logits_f32seq(h_row: np.ndarray, W: np.ndarray) -> np.ndarray:
+    """The same logits by sequential fp32 accumulation (to measure the effect of accumulation order)."""
+    h_row, W = _u16(h_row, "h_row"), _u16(W, "W")
+    V, d = W.shape
+    assert h_row.shape == (d,)
+    x = np.empty(V, dtype=np.float32)
+    _load().oracle_row_logits_f32seq(_ptr(h_row), _ptr(W), d, V, _ptr(x))
     return x
 
 

@@ -74,6 +74,19 @@ void oracle_row_logits(const uint16_t *h, const uint16_t *W, int32_t d,
   free(hd);
 }
 
+/* A second way to the same logits, for measuring how much the order of accumulation matters: plain fp32
+ * accumulation in ascending k (each product of two bf16 values is exact in fp32, so rounding happens only in
+ * the additions).  Not used for parity; the parity reference is oracle_row_logits. */
+void oracle_row_logits_f32seq(const uint16_t *h, const uint16_t *W, int32_t d,
+                              int32_t V, float *x) {
+  for (int32_t v = 0; v < V; ++v) {
+    const uint16_t *w = W + (size_t)v * (size_t)d;
+    float acc = 0.0f;
+    for (int32_t k = 0; k < d; ++k) acc += bf16_to_f32(h[k]) * bf16_to_f32(w[k]);
+    x[v] = acc;
+  }
+}
+
 /* Reduce one row of V fp32 logits to (tok, conf, lse, gap, rowmax). */
 void oracle_row_reduce(const float *x, int32_t V, int32_t *tok, float *conf,
                        float *lse, float *gap, float *rowmax) {

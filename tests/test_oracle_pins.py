@@ -93,6 +93,25 @@ def test_logits_fp64_accumulation_not_fp32():
     assert x[0] != np.float32(256.0)              # what step-by-step fp32 adds would give
 
 
+def test_sequential_fp32_mode_shows_what_accumulation_order_costs():
+    """The auxiliary fp32-sequential logits: wrong exactly where the fp64 reference is right (the planted sum),
+    identical on integer inputs, and within ~1e-5 of the reference on benchmark-like rows (d = 4096) -- three
+    orders below the parity tolerances, which is why a GPU's own accumulation order is acceptable."""
+    d = 16
+    h = np.ones(d, np.float32)
+    w = np.array([[256.0] + [2.0 ** -18] * (d - 1)], np.float32)
+    assert oracle.row_logits_f32seq(bits(h), bits(w))[0] == np.float32(256.0)      # every small addend is lost
+    rng = np.random.default_rng(9)
+    hi = rng.integers(-4, 5, 96).astype(np.float32)
+    wi = rng.integers(-3, 4, (40, 96)).astype(np.float32)
+    assert np.array_equal(oracle.row_logits_f32seq(bits(hi), bits(wi)), oracle.row_logits(bits(hi), bits(wi)))
+    H = rand_bf16((1, 4096), 1.0, 5)
+    W = rand_bf16((2048, 4096), 4096 ** -0.5, 6)
+    hb, wb = H.view(torch.uint16).numpy()[0], W.view(torch.uint16).numpy()
+    diff = np.abs(oracle.row_logits_f32seq(hb, wb).astype(np.float64) - oracle.row_logits(hb, wb))
+    assert 0 < diff.max() < 2e-5
+
+
 # ---------------------------------------------------------------- library special cases
 def test_logits_vs_torch_fp64_matmul():
     H = rand_bf16((7, 320), 1.0, 1)
