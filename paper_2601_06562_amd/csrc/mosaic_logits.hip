@@ -65,7 +65,9 @@ struct KernelParams {
   int32_t max_rows;
   int32_t splits;      // S
   int32_t panel;       // row tiles scheduled side by side
-  int32_t vocab_tiles; // ceil(V / 256)
+  int32_t vocab_tiles; // vocabulary tiles this launch covers (all ceil(V / 256) of them unless the launch is one of a pair)
+  int32_t tile_first;  // first of those tiles
+  int32_t split_first; // partial slot of this launch's split 0
   int32_t c_pad;       // row capacity of the partial arrays
   float* part_m;
   float* part_s;
@@ -308,8 +310,8 @@ __global__ __launch_bounds__(kThreads) void masked_logits_kernel(const KernelPar
     const int hp = (n_tt - pnl * A) < A ? (n_tt - pnl * A) : A;
     const int sp = ul / hp;
     const int tt = pnl * A + ul % hp;
-    const int vt0 = (int)(((int64_t)sp * p.vocab_tiles) / S);
-    const int vt1 = (int)(((int64_t)(sp + 1) * p.vocab_tiles) / S);
+    const int vt0 = p.tile_first + (int)(((int64_t)sp * p.vocab_tiles) / S);
+    const int vt1 = p.tile_first + (int)(((int64_t)(sp + 1) * p.vocab_tiles) / S);
     const int ntile = vt1 - vt0;
     const int total_steps = ntile * nk;
 
@@ -469,7 +471,7 @@ __global__ __launch_bounds__(kThreads) void masked_logits_kernel(const KernelPar
 #pragma unroll
       for (int bj = 0; bj < 2; ++bj) {
         const int e = (wt * 2 + bj) * 32 + l32;
-        const int64_t slot = (int64_t)sp * p.c_pad + tt * kTileRows + e;
+        const int64_t slot = (int64_t)(p.split_first + sp) * p.c_pad + tt * kTileRows + e;
         if constexpr (SAMPLE) {
           merge_ms(run_m[bj], run_s[bj], red_m[e], red_s[e]);
           merge_pick(run_ym[bj], run_xa[bj], run_i[bj], red_ym[e], red_xa[e], red_i[e]);
@@ -862,6 +864,8 @@ int launch_masked_logits(const LogitsArgs& a, const mosaic_plan& plan, hipStream
   p.splits = plan.vocab_splits;
   p.panel = plan.tile_panel;
   p.vocab_tiles = (a.V + kTileVocab - 1) / kTileVocab;
+  p.tile_first = 0;
+  p.split_first = 0;
   p.c_pad = plan.rows_per_chunk;
   p.part_m = static_cast<float*>(a.workspace);
   p.part_s = p.part_m + (int64_t)plan.vocab_splits * plan.rows_per_chunk;
@@ -876,28 +880,54 @@ int launch_masked_logits(const LogitsArgs& a, const mosaic_plan& plan, hipStream
   p.part_ym = reinterpret_cast<float*>(p.part_i + (int64_t)plan.vocab_splits * plan.rows_per_chunk);
   p.part_xa = p.part_ym + (int64_t)plan.vocab_splits * plan.rows_per_chunk;
 
-  // The hand-scheduled 4-wave kernel needs whole vocabulary tiles and 32-bit row offsets; everything
-  // else (and plans that ask for it) goes to the general 8-wave kernel.
-  const bool fast = (plan.flags & MOSAIC_PLAN_GENERAL_KERNEL) == 0 && a.V % kTileVocab == 0 &&
-                    (uint64_t)a.T * (uint64_t)p.ldh_bytes < ((uint64_t)1 << 32) &&
-                    (uint64_t)kTileVocab * (uint64_t)a.d * 2u < ((uint64_t)1 << 32);
+  // The hand-scheduled 4-wave kernel needs whole vocabulary tiles and 32-bit row offsets.  A vocabulary with a
+  // ragged last tile is covered by a pair of launches: the 4-wave kernel on the whole tiles with S - 1 splits and
+  // the general 8-wave kernel on the last tile as split S - 1.  Everything else (and plans that ask for it) goes
+  // to the general kernel alone.
+  const bool fast_ok = (plan.flags & MOSAIC_PLAN_GENERAL_KERNEL) == 0 &&
+                       (uint64_t)a.T * (uint64_t)p.ldh_bytes < ((uint64_t)1 << 32) &&
+                       (uint64_t)kTileVocab * (uint64_t)a.d * 2u < ((uint64_t)1 << 32);
+  const bool fast = fast_ok && a.V % kTileVocab == 0;
+  const bool paired = fast_ok && !fast && p.vocab_tiles >= 2 && plan.vocab_splits >= 2;
+  // The selector gives a ragged vocabulary one split more than fills the chip (for the pair's second launch);
+  // the general kernel alone works best without it.
+  if (!fast && !paired && a.V % kTileVocab != 0 && p.vocab_tiles >= 2 && p.splits >= 2) p.splits -= 1;
+  KernelParams body = p, tail = p;   // the two launches of a pair
+  if (paired) {
+    body.vocab_tiles = p.vocab_tiles - 1;
+    body.splits = plan.vocab_splits - 1;
+    if (body.splits > body.vocab_tiles) body.splits = body.vocab_tiles;
+    tail.vocab_tiles = 1;
+    tail.tile_first = p.vocab_tiles - 1;
+    tail.splits = 1;
+    tail.split_first = body.splits;
+    p.splits = body.splits + 1;        // what the merge reads
+  }
   for (int c = 0; c < plan.num_chunks; ++c) {
     const int64_t row0 = (int64_t)c * plan.rows_per_chunk;
     if (row0 >= a.max_rows) break;
-    p.row0 = (int32_t)row0;
+    p.row0 = body.row0 = tail.row0 = (int32_t)row0;
     int64_t cap = a.max_rows - row0;
     if (cap > plan.rows_per_chunk) cap = plan.rows_per_chunk;
     const int64_t tiles = (cap + kTileRows - 1) / kTileRows;
-    int64_t grid = tiles * plan.vocab_splits;
+    const KernelParams& q = paired ? body : p;
+    int64_t grid = tiles * q.splits;
     if (grid > plan.grid) grid = plan.grid;
-    if (fast && sample)
-      hipLaunchKernelGGL((masked_logits_kernel_w4<true>), dim3((unsigned)grid), dim3(256), 0, stream, p);
-    else if (fast)
-      hipLaunchKernelGGL((masked_logits_kernel_w4<false>), dim3((unsigned)grid), dim3(256), 0, stream, p);
+    if ((fast || paired) && sample)
+      hipLaunchKernelGGL((masked_logits_kernel_w4<true>), dim3((unsigned)grid), dim3(256), 0, stream, q);
+    else if (fast || paired)
+      hipLaunchKernelGGL((masked_logits_kernel_w4<false>), dim3((unsigned)grid), dim3(256), 0, stream, q);
     else if (sample)
       hipLaunchKernelGGL((masked_logits_kernel<3, 2, true>), dim3((unsigned)grid), dim3(kThreads), 0, stream, p);
     else
       hipLaunchKernelGGL((masked_logits_kernel<3, 2, false>), dim3((unsigned)grid), dim3(kThreads), 0, stream, p);
+    if (paired) {
+      const int64_t tgrid = tiles < plan.grid ? tiles : plan.grid;
+      if (sample)
+        hipLaunchKernelGGL((masked_logits_kernel<3, 2, true>), dim3((unsigned)tgrid), dim3(kThreads), 0, stream, tail);
+      else
+        hipLaunchKernelGGL((masked_logits_kernel<3, 2, false>), dim3((unsigned)tgrid), dim3(kThreads), 0, stream, tail);
+    }
     hipLaunchKernelGGL(combine_kernel, dim3((unsigned)((cap + kCombineRows - 1) / kCombineRows)), dim3(256), 0, stream, p);
   }
   return hipGetLastError() == hipSuccess ? 0 : -1;

@@ -53,7 +53,12 @@ extern "C" int mosaic_plan_workspace(int64_t T, int64_t max_rows, int32_t d, int
     const int64_t per = (rows + K - 1) / K;
     const int64_t C = (per + MOSAIC_ROW_TILE - 1) / MOSAIC_ROW_TILE * MOSAIC_ROW_TILE;
     const int64_t row_tiles = C / MOSAIC_ROW_TILE;
-    int64_t S = choose_vocab_splits(row_tiles, vocab_tiles, num_cus);
+    // A vocabulary with a ragged last tile is run as a pair of launches: the whole tiles in S - 1 splits chosen to
+    // fill the chip, the last tile as one more split.
+    const bool ragged = V % MOSAIC_VOCAB_TILE != 0 && vocab_tiles >= 2;
+    int64_t S = ragged ? choose_vocab_splits(row_tiles, vocab_tiles - 1, num_cus) + 1
+                       : choose_vocab_splits(row_tiles, vocab_tiles, num_cus);
+    if (S > MOSAIC_MAX_VOCAB_SPLITS) S = MOSAIC_MAX_VOCAB_SPLITS;
     if (budget_bytes > 0) {
       const int64_t fit = budget_bytes / partials_bytes(C, 1);  // splits the budget allows
       if (fit < S) S = fit;
