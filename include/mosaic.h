@@ -19,8 +19,10 @@
  *     and keeps no state between calls.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
  *     only enqueue work on it and return; they never synchronise the device.
- *   - Return value: MOSAIC_OK (0) or a negative mosaic_status.  On error nothing has
- *     been enqueued.  mosaic_status_string() names a status.
+ *   - Return value: MOSAIC_OK (0) or a negative mosaic_status.  Argument and shape errors
+ *     are found before anything is enqueued; MOSAIC_ERR_HIP reports a failed launch, and
+ *     earlier launches of the same call may then already be in the stream (outputs are
+ *     unspecified).  mosaic_status_string() names a status.
  *   - T = flat number of positions (a batch is the concatenation of its sequences,
  *     no padding -- paper section 5.1), M = number of masked positions, d = hidden
  *     size, V = vocabulary size.
