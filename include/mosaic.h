@@ -129,7 +129,8 @@ int mosaic_mask_compact(const uint8_t *mask, int64_t T, int32_t *out_idx, int32_
  *   workspace  dev, >= plan->workspace_bytes, 16-byte aligned; contents are scratch.  Calls that may run
  *              concurrently (different streams) need workspaces of their own
  * max_rows == 0 or V == 0 enqueue nothing.  Inputs must be finite; a NaN or Inf in a
- * row gives unspecified values for that row only.  Errors: INVALID_ARG,
+ * row gives unspecified values for that row only.  The accuracy the tests hold the call to (2e-3 absolute
+ * on out_lse and out_conf) is met for logits of magnitude up to a few thousand.  Errors: INVALID_ARG,
  * UNSUPPORTED_SHAPE (d % MOSAIC_K_TILE, ld_h, T >= 2^31, V >= 2^31 - 256),
  * WORKSPACE_TOO_SMALL, HIP.
  */

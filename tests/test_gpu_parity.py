@@ -287,3 +287,24 @@ def test_mfma_probe_runs_and_reports_its_flops():
     torch.cuda.synchronize()
     assert flop == 100 * 256 * 4 * 64 * 16384
     assert bool(torch.isfinite(sink).all())            # every lane of every workgroup stored its sum
+
+
+def test_large_common_offset_stays_within_tolerance():
+    """All logits of a row shifted by a large constant (a hidden component along a direction every LM-head row
+    shares): the exponent of exp(x - max) is formed from values of magnitude ~1000, where fp32 rounding of the
+    products is largest; lse and conf must still meet the tolerances."""
+    print("large offset", flush=True)
+    rng = np.random.default_rng(12)
+    T, d, V = 300, 128, 4096
+    H = rng.standard_normal((T, d)).astype(np.float32)
+    W = (rng.standard_normal((V, d)) * d ** -0.5).astype(np.float32)
+    W[:, 0] = 1.0
+    H[:, 0] = np.where(np.arange(T) % 2 == 0, 1024.0, -768.0)
+    hidden, w = bf16(H), bf16(W)
+    mask = torch.ones(T, dtype=torch.uint8, device=DEV)
+    out = run_hip(hidden, w, mask)
+    want = oracle.positions(workloads.bf16_bits(hidden), workloads.bf16_bits(w), np.arange(T))
+    assert np.abs(want.lse).min() > 700
+    stats = check_against_oracle(dict(tok=out["tok"][:T], conf=out["conf"][:T], lse=out["lse"][:T]), want,
+                                 what="large offset")
+    print(stats, flush=True)
