@@ -120,3 +120,50 @@ def test_hidden_tensor_between_2_and_4_gib_on_the_fast_path():
     print(stats, flush=True)
     del hidden
     torch.cuda.empty_cache()
+
+
+def test_dream_shape_shifted_prediction_and_sampling():
+    """The Dream-shaped workload end to end as Dream decodes: positions predicted from the hidden row before them
+    (compact -> shifted gather list -> fused pass), greedy and with temperature sampling, on sampled rows."""
+    import oracle
+    from paper_2601_06562_amd import binding
+    name = "dream_late_step"
+    print(f"{name}: shifted + sampling, generating", flush=True)
+    wl = workloads.make(name, device=DEV)
+    M = wl.M
+    seq_starts = torch.tensor([0, wl.T], dtype=torch.int32, device=DEV)
+    op = binding.MaskOnlyLogits(wl.T, wl.d, wl.V, max_rows=M, device=DEV, sampling=True)
+    binding.mosaic_mask_compact(wl.mask, op.idx, op.count, op.scratch)
+    gather = torch.empty_like(op.idx)
+    binding.mosaic_shift_indices(op.idx, op.count, op.max_rows, seq_starts, gather)
+    binding.mosaic_masked_logits_reduce(wl.hidden, wl.w, gather, op.count, op.max_rows, op.token, op.conf, op.lse,
+                                        op.plan, op.workspace)
+    torch.cuda.synchronize()
+    assert int(op.count.item()) == M
+    idx = op.idx[:M].cpu().numpy()
+    rows_read = gather[:M].cpu().numpy()
+    assert np.array_equal(rows_read, oracle.shift_indices(idx, np.array([0, wl.T], np.int32)))
+    rng = np.random.default_rng(23)
+    rows = sample_rows(M, rng)
+    w_bits = workloads.bf16_bits(wl.w)
+    want, logits = oracle_rows(wl.hidden, w_bits, rows_read[rows], return_logits=True)
+    stats = check_against_oracle(dict(tok=op.token[:M].cpu().numpy()[rows], conf=op.conf[:M].cpu().numpy()[rows],
+                                      lse=op.lse[:M].cpu().numpy()[rows]), want, logits, what=name + " shifted")
+    print(f"{name} shifted: {stats}", flush=True)
+    # the same gather list under sampling: the noise is keyed by the row that is READ (the entry of the list)
+    tau, seed = 0.7, 20260107
+    binding.mosaic_masked_logits_sample(wl.hidden, wl.w, gather, op.count, op.max_rows, tau, seed, op.token, op.conf,
+                                        op.lse, op.plan, op.workspace)
+    torch.cuda.synchronize()
+    tok, conf, lse = op.token[:M].cpu().numpy(), op.conf[:M].cpu().numpy(), op.lse[:M].cpu().numpy()
+    strict = 0
+    for k, j in enumerate(rows):
+        x = logits[k]
+        tok_o, conf_o, lse_o, gap_o = oracle.row_sample(x, tau, seed, int(rows_read[j]))
+        assert abs(float(lse[j]) - lse_o) <= 2e-3
+        if gap_o > 1e-3 * (1 + tau):
+            strict += 1
+            assert int(tok[j]) == tok_o, (j, int(tok[j]), tok_o, gap_o)
+            assert abs(float(conf[j]) - conf_o) <= 2e-3 and abs(float(conf[j]) - conf_o) <= 5e-3 * max(conf_o, 1e-30)
+    assert strict >= 0.9 * len(rows)
+    print(f"{name} shifted + sampling: {strict} strict rows of {len(rows)}", flush=True)
