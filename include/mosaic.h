@@ -10,8 +10,8 @@
  * the paper's kernel: the vocabulary reduction that sampling needs (arg-max id, its
  * soft-max probability, the row's log-sum-exp) is fused into the GEMM epilogue, so
  * neither [T,V] nor [M,V] logits ever exist in memory.  Section 4.4's chunking of
- * the logits operator along the sequence dimension (chunk count K_logits, "lazy":
- * off unless memory is short, minimal K otherwise) appears as mosaic_plan_workspace.
+ * the logits operator along the sequence dimension (chunk count K_logits: chunking stays
+ * off unless memory is short, and K is then the smallest that fits) appears as mosaic_plan_workspace.
  *
  * Conventions for every call
  *   - "dev" pointers are device (HBM) pointers owned by the CALLER; "host" pointers
@@ -72,8 +72,8 @@ typedef struct {
 #define MOSAIC_PLAN_GENERAL_KERNEL 1
 
 /*
- * Chunk-size selector (paper section 4.4, "lazy chunking strategy" and "online
- * bottleneck-driven search", restricted to the one chunkable operator on this path).
+ * Chunk-size selector (paper section 4.4: the lazy chunking strategy and its
+ * bottleneck-driven search, restricted to the one chunkable operator on this path).
  * Host-only, pure function.  Starts from K = 1 (chunking off); while the workspace of
  * one chunk of C = roundup(ceil(max_rows / K), MOSAIC_ROW_TILE) rows exceeds
  * budget_bytes even with a single vocabulary split, K is raised by one; stops at the
@@ -93,8 +93,8 @@ int mosaic_plan_workspace(int64_t T, int64_t max_rows, int32_t d, int32_t V, int
                           int32_t num_cus, mosaic_plan *out_plan);
 
 /*
- * Stream compaction of the mask (paper section 4.2: the kernel is handed "mask indices
- * (identifying masked tokens)"; this call makes them).  Exclusive prefix sum over
+ * Stream compaction of the mask (paper section 4.2: the gather-GEMM kernel takes the list of
+ * masked positions as an input and does not say who builds it; this call builds it).  Exclusive prefix sum over
  * mask[t] != 0, then out_idx[scan[t]] = t: the masked positions in ascending order,
  * bit-exact.  Any nonzero byte counts as masked.
  *   mask       dev uint8[T]
@@ -110,8 +110,8 @@ int mosaic_mask_compact(const uint8_t *mask, int64_t T, int32_t *out_idx, int32_
 
 /*
  * Mask-only logits with the vocabulary reduction fused in (paper section 4.2 for the
- * gather-GEMM; the reduction is this library's reading of section 2.1's "tokens are
- * sampled from the logits": greedy).  For every j < *count, with t = idx[j]:
+ * gather-GEMM; section 2.1 only says that a step draws tokens from the logits, and the
+ * reduction here is this library's reading of that: greedy).  For every j < *count, with t = idx[j]:
  *   x[v]        = sum_k hidden[t,k] * w[v,k]      bf16 x bf16, fp32 accumulation, no bias
  *   out_token[j] = lowest v attaining max_v x[v]
  *   out_lse[j]   = log sum_v exp(x[v])

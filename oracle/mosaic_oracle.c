@@ -43,8 +43,8 @@ static inline float bf16_to_f32(uint16_t b) {
   return f;
 }
 
-/* Stable selection of the masked positions (paper section 4.2: the kernel is
- * handed "mask indices"; ascending order is the reading taken here).
+/* Stable selection of the masked positions (paper section 4.2: the kernel takes the
+ * list of masked positions as an input; ascending order is the reading taken here).
  * mask: T bytes, nonzero = still masked.  idx: room for T entries.
  * Returns M, the number of masked positions. */
 int64_t oracle_mask_select(const uint8_t *mask, int64_t T, int32_t *idx) {

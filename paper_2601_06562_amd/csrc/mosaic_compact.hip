@@ -1,7 +1,7 @@
 // Stream compaction of the mask into ascending indices of masked positions.
 //
-// Paper section 4.2: the gather-GEMM kernel is handed "mask indices (identifying masked
-// tokens)"; the paper leaves their production to the framework.  Here it is an explicit
+// Paper section 4.2: the gather-GEMM kernel takes the list of masked positions as an input;
+// the paper leaves its production to the framework.  Here it is an explicit
 // exclusive prefix sum over (mask[t] != 0) followed by a scatter that never touches the host:
 // one single-block launch for up to 65536 positions (a denoising step of one long sequence),
 // otherwise three small launches (per-block counts, a scan of those counts, the scatter).

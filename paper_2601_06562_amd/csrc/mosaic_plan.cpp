@@ -1,7 +1,7 @@
 // Host-side chunk-size selector for the mask-only logits path.
 //
 // Paper section 4.4: chunking of the logits operator along the sequence dimension is off by
-// default ("lazy") and switched on only when memory is short; the search raises the chunk count of
+// default and switched on only when memory is short; the search raises the chunk count of
 // the operator that forms the peak by one, re-evaluates the footprint, and stops at the first
 // configuration that fits, or fails when only non-chunkable memory is left.  On this path the one
 // chunkable buffer is the array of partial (max, sum-exp, arg-max) triples, 12 bytes per row and

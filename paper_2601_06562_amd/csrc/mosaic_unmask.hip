@@ -1,6 +1,6 @@
 // The tail of a denoising step, after mask-only logits: pick the positions to unmask and write their
-// tokens (paper section 2.1: "tokens are sampled from the logits and used to replace a selected subset of
-// the [MASK] positions"), and the index shift of Dream-style prediction (section 4.5, last paragraph).
+// tokens (paper section 2.1: a step's drawn tokens replace a chosen subset of the still-masked positions;
+// which subset is left open), and the index shift of Dream-style prediction (section 4.5, last paragraph).
 // Integer / byte work: results are bit-exact by construction.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
