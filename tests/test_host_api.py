@@ -195,3 +195,13 @@ def test_vmm_entry_points_validate_their_arguments():
     assert L.mosaic_vmm_committed_bytes(None) == 0 and L.mosaic_vmm_reserved_bytes(None) == 0
     assert L.mosaic_vmm_granularity(None) == 0
     assert L.mosaic_vmm_destroy(None) == binding.MOSAIC_OK
+
+
+def test_selector_keeps_at_least_four_splits_for_cache_sharing():
+    """Many row tiles would balance with a single split each, but the workgroups behind one L2 then share no hidden
+    tile; the selector keeps four splits wherever the vocabulary has four tiles (a byte budget may still cut them)."""
+    for rows in (65536, 131072, 16384 * 3):
+        assert binding.mosaic_plan_workspace(rows, rows, 4096, 126464, 0).vocab_splits >= 4
+    assert binding.mosaic_plan_workspace(65536, 65536, 4096, 512, 0).vocab_splits == 2        # only two tiles
+    tight = binding.mosaic_plan_workspace(65536, 65536, 4096, 126464, 12 * 65536)            # budget for one split
+    assert tight.vocab_splits == 1 and tight.num_chunks == 1
