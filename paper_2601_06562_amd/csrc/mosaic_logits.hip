@@ -135,6 +135,17 @@ __device__ __forceinline__ void gumbel4(uint32_t k0, uint32_t k1, uint32_t pos, 
   }
 }
 
+// Workgroups are dealt to the 8 XCDs round-robin by id, and the workgroups of one XCD share an L2.  This maps
+// workgroup b of a grid of G to a position such that each XCD's workgroups hold one contiguous range of positions
+// (XCD x owns ceil((G - x) / 8) of them), so that consecutive work units -- which share LM-head and hidden tiles --
+// meet in one L2.  A bijection on [0, G) for any G.
+__device__ __forceinline__ int xcd_contiguous_position(int b, int G) {
+  const int x = b & 7;
+  int first = 0;
+  for (int y = 0; y < x; ++y) first += (G - y + 7) >> 3;
+  return first + (b >> 3);
+}
+
 template <int N>
 __device__ __forceinline__ void wait_vm() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
@@ -285,8 +296,7 @@ __global__ __launch_bounds__(kThreads) void masked_logits_kernel(const KernelPar
   const int n_tt = (rows + kTileRows - 1) / kTileRows;
 
   const int G = gridDim.x;
-  int pos = blockIdx.x;
-  if ((G & 7) == 0) pos = (int)(blockIdx.x & 7) * (G >> 3) + (int)(blockIdx.x >> 3);
+  const int pos = xcd_contiguous_position((int)blockIdx.x, G);
   const int S = p.splits;
   const int n_units = n_tt * S;
   const int A = p.panel < n_tt ? p.panel : n_tt;
@@ -606,8 +616,7 @@ __global__ __launch_bounds__(256) void masked_logits_kernel_w4(const KernelParam
   const int n_tt = (rows + kTileRows - 1) / kTileRows;
 
   const int G = gridDim.x;
-  int pos = blockIdx.x;
-  if ((G & 7) == 0) pos = (int)(blockIdx.x & 7) * (G >> 3) + (int)(blockIdx.x >> 3);
+  const int pos = xcd_contiguous_position((int)blockIdx.x, G);
   const int S = p.splits;
   const int n_units = n_tt * S;
   const int A = p.panel < n_tt ? p.panel : n_tt;
