@@ -61,9 +61,6 @@ def _load():
         lib.oracle_gumbel.argtypes = [ctypes.c_uint64, i32, i32]
         lib.oracle_row_sample.restype = None
         lib.oracle_row_sample.argtypes = [p, i32, ctypes.c_double, ctypes.c_uint64, i32, p, p, p, p]
-        lib.oracle_positions_sample.restype = ctypes.c_int
-        lib.oracle_positions_sample.argtypes = [p, i64, i32, i64, p, i32, p, i64, ctypes.c_double, ctypes.c_uint64,
-                                                p, p, p, p]
         lib.oracle_num_threads.restype = ctypes.c_int
         lib.oracle_num_threads.argtypes = []
         _lib = lib
@@ -219,19 +216,3 @@ def row_sample(x, tau, seed, position):
     _load().oracle_row_sample(_ptr(x), x.size, float(tau), int(seed), int(position), ctypes.byref(tok),
                               ctypes.byref(conf), ctypes.byref(lse), ctypes.byref(gap))
     return int(tok.value), float(conf.value), float(lse.value), float(gap.value)
-
-
-def positions_sample(H, W, pos, tau, seed):
-    """Sampled token, its probability, lse and the perturbed top-2 gap at the listed positions."""
-    H, W = _u16(H, "H"), _u16(W, "W")
-    T, d = H.shape
-    V, _ = W.shape
-    pos = np.ascontiguousarray(pos, dtype=np.int64)
-    n = pos.size
-    tok, conf = np.empty(n, np.int32), np.empty(n, np.float32)
-    lse, gap = np.empty(n, np.float32), np.empty(n, np.float32)
-    rc = _load().oracle_positions_sample(_ptr(H), T, d, d, _ptr(W), V, _ptr(pos), n, float(tau), int(seed),
-                                         _ptr(tok), _ptr(conf), _ptr(lse), _ptr(gap))
-    if rc != 0:
-        raise ValueError("position out of range")
-    return tok, conf, lse, gap

@@ -278,19 +278,3 @@ void oracle_row_sample(const float *x, int32_t V, double tau, uint64_t seed, int
   *conf = (float)exp((double)x[arg] - l);
   *ygap = (V > 1) ? (float)(best - second) : INFINITY;
 }
-
-/* Sampling at the listed positions (restriction of the full computation, as oracle_positions). */
-int oracle_positions_sample(const uint16_t *H, int64_t T, int32_t d, int64_t ld_h, const uint16_t *W, int32_t V,
-                            const int64_t *pos, int64_t n, double tau, uint64_t seed, int32_t *tok, float *conf,
-                            float *lse, float *ygap) {
-  for (int64_t j = 0; j < n; ++j)
-    if (pos[j] < 0 || pos[j] >= T) return -1;
-#pragma omp parallel for schedule(dynamic, 1)
-  for (int64_t j = 0; j < n; ++j) {
-    float *x = (float *)malloc(sizeof(float) * (size_t)V);
-    oracle_row_logits(H + (size_t)pos[j] * (size_t)ld_h, W, d, V, x);
-    oracle_row_sample(x, V, tau, seed, (int32_t)pos[j], &tok[j], &conf[j], &lse[j], &ygap[j]);
-    free(x);
-  }
-  return 0;
-}

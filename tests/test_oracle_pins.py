@@ -317,6 +317,25 @@ def test_uniform_and_gumbel_statistics():
     assert len({oracle.uniform(1, 2, 3), oracle.uniform(2, 2, 3), oracle.uniform(1, 3, 3), oracle.uniform(1, 2, 4)}) == 4
 
 
+def test_uniform_counter_layout_and_gumbel_inverse_cdf():
+    """The uniform is word v % 4 of the (separately pinned) Philox block at counter (v / 4, position, 0, 0) under the
+    key (seed low, seed high), reduced to 23 bits plus one half; the Gumbel variate is the one whose distribution
+    function exp(-exp(-g)) gives that uniform back."""
+    seed = 0x0123456789ABCDEF
+    for position, v in ((0, 0), (5, 3), (5, 4), (77, 126463), (2 ** 31 - 1, 6), (131071, 152063)):
+        words = oracle.philox4x32_10([v // 4, position, 0, 0], [seed & 0xFFFFFFFF, seed >> 32])
+        u = oracle.uniform(seed, position, v)
+        k = u * 2 ** 23 - 0.5
+        assert k == int(k) and 0 <= k < 2 ** 23                   # 23 bits, never 0 or 1
+        assert int(k) == int(words[v % 4]) >> 9
+        g = oracle.gumbel(seed, position, v)
+        assert math.exp(-math.exp(-g)) == pytest.approx(u, rel=1e-12)
+    # the four ids of one counter block take the four words in order, the next id starts a new block
+    block = oracle.philox4x32_10([10, 9, 0, 0], [1, 0])
+    assert [int(oracle.uniform(1, 9, 40 + j) * 2 ** 23 - 0.5) for j in range(4)] == [int(w) >> 9 for w in block]
+    assert int(oracle.uniform(1, 9, 44) * 2 ** 23 - 0.5) == int(oracle.philox4x32_10([11, 9, 0, 0], [1, 0])[0]) >> 9
+
+
 def test_sampling_reduces_to_greedy_and_follows_softmax():
     rng = np.random.default_rng(8)
     x = rng.standard_normal(300).astype(np.float32)
