@@ -15,10 +15,13 @@
  *
  * Conventions for every call
  *   - "dev" pointers are device (HBM) pointers owned by the CALLER; "host" pointers
- *     are ordinary host memory.  The library allocates and frees no device memory
- *     and keeps no state between calls.
+ *     are ordinary host memory.  The compute calls allocate and free no device memory
+ *     and keep no state between calls.  The one exception is the mosaic_vmm_* object at
+ *     the end of this header: it owns a virtual address range and the physical pages
+ *     mapped behind it, and mosaic_vmm_resize / mosaic_vmm_destroy wait for the device.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
- *     only enqueue work on it and return; they never synchronise the device.
+ *     only enqueue work on it and return; they never synchronise the device
+ *     (mosaic_vmm_* excepted, as above).
  *   - Return value: MOSAIC_OK (0) or a negative mosaic_status.  Argument and shape errors
  *     are found before anything is enqueued; MOSAIC_ERR_HIP reports a failed launch, and
  *     earlier launches of the same call may then already be in the stream (outputs are
@@ -63,13 +66,16 @@ typedef struct {
   int32_t vocab_splits;    /* S: vocabulary ranges whose partial results are merged     */
   int32_t tile_panel;      /* row tiles scheduled side by side (cache-sharing group)    */
   int32_t grid;            /* persistent workgroups launched per chunk                  */
-  int32_t flags;           /* 0, or MOSAIC_PLAN_GENERAL_KERNEL (see below)                */
+  int32_t flags;           /* MOSAIC_PLAN_* bits (see below)                              */
 } mosaic_plan;
 
 /* plan.flags bit: use the general 8-wave kernel even where the hand-scheduled 4-wave kernel applies
  * (it applies when V is a multiple of MOSAIC_VOCAB_TILE and hidden spans less than 4 GiB).  Both give
  * the same results; the flag exists for testing and tuning. */
 #define MOSAIC_PLAN_GENERAL_KERNEL 1
+/* plan.flags bit, set by the selector: the plan was sized for a sampling step (20 bytes per row and
+ * vocabulary split in workspace_bytes instead of 12). */
+#define MOSAIC_PLAN_SAMPLING 2
 
 /*
  * Chunk-size selector (paper section 4.4: the lazy chunking strategy and its
@@ -80,17 +86,21 @@ typedef struct {
  * first K that fits (the minimal one) and fails with MOSAIC_ERR_WORKSPACE_TOO_SMALL
  * when even one row tile with one split does not fit (the non-chunkable floor).
  * The workspace is 12 * S * C bytes (one (max, sum-exp, arg-max) triple per row and
- * vocabulary split) -- never O(C * V).
+ * vocabulary split) -- never O(C * V); 20 * S * C when the plan is for a sampling step
+ * (mosaic_masked_logits_sample with temperature > 0 keeps two more values per partial), so
+ * that the budget bounds what that call really needs.
  *   T          total positions, >= 0, < 2^31
  *   max_rows   host-side upper bound on M (the search in the paper is driven by the
  *              number of masks and the number of tokens; pass T if M is unknown), 0..T
  *   d, V       hidden and vocabulary size; d must be a multiple of MOSAIC_K_TILE
  *   budget_bytes  <= 0 means unbounded
  *   num_cus    compute units to schedule for; <= 0 means 256 (one MI355X)
+ *   sampling   0: plan for mosaic_masked_logits_reduce; 1: plan for mosaic_masked_logits_sample with
+ *              temperature > 0 (sets MOSAIC_PLAN_SAMPLING); anything else is INVALID_ARG
  *   out_plan   host pointer, written on success
  */
 int mosaic_plan_workspace(int64_t T, int64_t max_rows, int32_t d, int32_t V, int64_t budget_bytes,
-                          int32_t num_cus, mosaic_plan *out_plan);
+                          int32_t num_cus, int32_t sampling, mosaic_plan *out_plan);
 
 /*
  * Stream compaction of the mask (paper section 4.2: the gather-GEMM kernel takes the list of
@@ -120,7 +130,9 @@ int mosaic_mask_compact(const uint8_t *mask, int64_t T, int32_t *out_idx, int32_
  *   hidden     dev bf16[T, d], row-major, row stride ld_h elements (ld_h >= d,
  *              ld_h % 8 == 0), 16-byte aligned; only rows named by idx are read
  *   w          dev bf16[V, d], row-major, dense, 16-byte aligned
- *   idx        dev int32[>= *count], every entry in [0, T) (as mosaic_mask_compact makes)
+ *   idx        dev int32[>= *count], every entry in [0, T) (as mosaic_mask_compact makes).  An entry
+ *              outside that range in a caller-built list is clamped to it on the device: the row's
+ *              results are then those of row 0 or T - 1, and nothing outside `hidden` is read
  *   count      dev int32[1], read on the device: 0 <= *count <= max_rows.  If it exceeds
  *              max_rows only the first max_rows rows are produced.
  *   max_rows   the bound the plan was made for
@@ -146,22 +158,28 @@ int mosaic_masked_logits_reduce(const void *hidden, int64_t T, int32_t d, int64_
  * no second pass over the logits).  For every j < *count, with t = idx[j] and x as above:
  *   g[v]         = -ln(-ln u[v]),  u[v] = ((word >> 9) + 1/2) * 2^-23, where word is output word v % 4 of
  *                  Philox4x32-10 (Salmon et al., SC'11) with key = (low, high 32 bits of seed) and
- *                  counter = (v / 4, t, 0, 0): the noise depends on (seed, position, id) only, not on the
- *                  chunking, the vocabulary split or the launch shape
+ *                  counter = (v / 4, n, 0, 0), n = noise_idx[j] (idx[j] when noise_idx is NULL): the noise
+ *                  depends on (seed, position, id) only, not on the chunking, the vocabulary split or the
+ *                  launch shape
  *   out_token[j] = lowest v attaining max_v ( x[v] + temperature * g[v] )      (fp32)
  *   out_lse[j]   = log sum_v exp(x[v])                                          (of the unperturbed logits)
  *   out_conf[j]  = exp(x[out_token[j]] - out_lse[j])
  * temperature == 0 is exactly mosaic_masked_logits_reduce.  All other arguments are as there, except
+ *   noise_idx  dev int32[>= *count] or NULL: the position whose prediction row j is.  It differs from
+ *              idx[j] when the gather list is shifted (mosaic_shift_indices: position p reads hidden row
+ *              p - 1, and a sequence start s and s + 1 both read row s); passing the unshifted positions
+ *              here keeps the draws of different positions independent.  Any int32 value is valid
  *   workspace  dev, >= mosaic_sample_workspace_bytes(plan) when temperature > 0 (20 bytes per row of a
- *              chunk and vocabulary split instead of 12), 16-byte aligned
+ *              chunk and vocabulary split instead of 12; plan->workspace_bytes already says so when the
+ *              plan was made with sampling = 1), 16-byte aligned
  *   seed       any value; callers advance it per denoising step
  * Additional errors: INVALID_ARG for a negative, NaN or infinite temperature.
  * mosaic_sample_workspace_bytes returns 0 for a NULL or unfilled plan.
  */
 int64_t mosaic_sample_workspace_bytes(const mosaic_plan *plan);
 int mosaic_masked_logits_sample(const void *hidden, int64_t T, int32_t d, int64_t ld_h, const void *w, int32_t V,
-                                const int32_t *idx, const int32_t *count, int64_t max_rows, float temperature,
-                                uint64_t seed, int32_t *out_token, float *out_conf, float *out_lse,
+                                const int32_t *idx, const int32_t *noise_idx, const int32_t *count, int64_t max_rows,
+                                float temperature, uint64_t seed, int32_t *out_token, float *out_conf, float *out_lse,
                                 const mosaic_plan *plan, void *workspace, int64_t workspace_bytes, void *stream);
 
 /*
@@ -175,7 +193,8 @@ int mosaic_masked_logits_sample(const void *hidden, int64_t T, int32_t d, int64_
  *   seq_starts                dev int32[num_seqs + 1], ascending flat positions delimiting the sequences
  *                             (seq_starts[0] = 0, seq_starts[num_seqs] = T)
  *   n_per_seq                 dev int32[num_seqs]; a sequence with fewer masked rows unmasks them all
- *   tokens                    dev int32[T], the token sequence(s); mask: dev uint8[T]
+ *   tokens                    dev int32[T], the token sequence(s); mask: dev uint8[T].  A row whose idx entry
+ *                             lies outside [0, T) is skipped
  * One workgroup per sequence; selection is exact (radix select on the fp32 bit patterns).
  * Errors: INVALID_ARG (null pointer, negative size, num_seqs < 1), UNSUPPORTED_SHAPE (T or max_rows >= 2^31).
  */
@@ -189,7 +208,8 @@ int mosaic_unmask_topn(const float *conf, const int32_t *token, const int32_t *i
  * the prediction for position p comes from the hidden state of position p - 1, except at the first
  * position of a sequence, which keeps its own.  out_gather[j] = that hidden row for idx[j]; pass it as
  * `idx` to mosaic_masked_logits_reduce (outputs stay in the order of the masked positions).
- *   idx, count, max_rows, seq_starts, num_seqs   as above;  out_gather: dev int32[max_rows]
+ *   idx, count, max_rows, seq_starts, num_seqs   as above;  out_gather: dev int32[max_rows], every entry
+ *                                                written is in [0, T) (T = seq_starts[num_seqs])
  */
 int mosaic_shift_indices(const int32_t *idx, const int32_t *count, int64_t max_rows, const int32_t *seq_starts,
                          int32_t num_seqs, int32_t *out_gather, void *stream);

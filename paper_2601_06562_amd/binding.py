@@ -24,6 +24,7 @@ ROW_TILE = 256
 VOCAB_TILE = 256
 K_TILE = 64
 PLAN_GENERAL_KERNEL = 1   # plan.flags bit: force the general 8-wave kernel
+PLAN_SAMPLING = 2         # plan.flags bit: sized for a sampling step (20 bytes per partial)
 
 EXPORTS = (
     "mosaic_status_string", "mosaic_plan_workspace", "mosaic_compact_scratch_bytes", "mosaic_mask_compact",
@@ -89,7 +90,7 @@ def lib():
         L.mosaic_version.restype = ctypes.c_int
         L.mosaic_version.argtypes = []
         L.mosaic_plan_workspace.restype = ctypes.c_int
-        L.mosaic_plan_workspace.argtypes = [i64, i64, i32, i32, i64, i32, ctypes.POINTER(MosaicPlan)]
+        L.mosaic_plan_workspace.argtypes = [i64, i64, i32, i32, i64, i32, i32, ctypes.POINTER(MosaicPlan)]
         L.mosaic_compact_scratch_bytes.restype = i64
         L.mosaic_compact_scratch_bytes.argtypes = [i64]
         L.mosaic_mask_compact.restype = ctypes.c_int
@@ -100,7 +101,7 @@ def lib():
         L.mosaic_sample_workspace_bytes.restype = i64
         L.mosaic_sample_workspace_bytes.argtypes = [ctypes.POINTER(MosaicPlan)]
         L.mosaic_masked_logits_sample.restype = ctypes.c_int
-        L.mosaic_masked_logits_sample.argtypes = [p, i64, i32, i64, p, i32, p, p, i64, ctypes.c_float, ctypes.c_uint64,
+        L.mosaic_masked_logits_sample.argtypes = [p, i64, i32, i64, p, i32, p, p, p, i64, ctypes.c_float, ctypes.c_uint64,
                                                   p, p, p, ctypes.POINTER(MosaicPlan), p, i64, p]
         L.mosaic_unmask_topn.restype = ctypes.c_int
         L.mosaic_unmask_topn.argtypes = [p, p, p, p, i64, p, i32, p, p, p, i64, p]
@@ -181,9 +182,9 @@ def _workspace_args(workspace):
     return _dev_ptr(workspace, "workspace"), workspace.numel() * workspace.element_size()
 
 
-def mosaic_plan_workspace(T, max_rows, d, V, budget_bytes=0, num_cus=0) -> MosaicPlan:
+def mosaic_plan_workspace(T, max_rows, d, V, budget_bytes=0, num_cus=0, sampling=False) -> MosaicPlan:
     plan = MosaicPlan()
-    _check(lib().mosaic_plan_workspace(T, max_rows, d, V, budget_bytes, num_cus, ctypes.byref(plan)),
+    _check(lib().mosaic_plan_workspace(T, max_rows, d, V, budget_bytes, num_cus, int(sampling), ctypes.byref(plan)),
            "mosaic_plan_workspace")
     return plan
 
@@ -229,8 +230,9 @@ def mosaic_sample_workspace_bytes(plan) -> int:
 
 
 def mosaic_masked_logits_sample(hidden, w, idx, count, max_rows, temperature, seed, out_token, out_conf, out_lse, plan,
-                                workspace, stream=None):
-    """As mosaic_masked_logits_reduce, with Gumbel-max sampling at `temperature` from the 64-bit `seed`."""
+                                workspace, stream=None, noise_idx=None):
+    """As mosaic_masked_logits_reduce, with Gumbel-max sampling at `temperature` from the 64-bit `seed`;
+    noise_idx (int32 device tensor or None) names the position each row predicts when idx is a shifted list."""
     T, d = hidden.shape
     V, d2 = w.shape
     if d != d2:
@@ -240,8 +242,8 @@ def mosaic_masked_logits_sample(hidden, w, idx, count, max_rows, temperature, se
     ld_h = hidden.stride(0) if T > 1 else d
     _check(lib().mosaic_masked_logits_sample(
         _dev_ptr(hidden, "hidden", torch.bfloat16), T, d, ld_h, _dev_ptr(w, "w", torch.bfloat16), V,
-        _dev_ptr(idx, "idx", torch.int32), _dev_ptr(count, "count", torch.int32), max_rows,
-        float(temperature), int(seed) & 0xFFFFFFFFFFFFFFFF,
+        _dev_ptr(idx, "idx", torch.int32), _dev_ptr(noise_idx, "noise_idx", torch.int32),
+        _dev_ptr(count, "count", torch.int32), max_rows, float(temperature), int(seed) & 0xFFFFFFFFFFFFFFFF,
         _dev_ptr(out_token, "out_token", torch.int32), _dev_ptr(out_conf, "out_conf", torch.float32),
         _dev_ptr(out_lse, "out_lse", torch.float32), ctypes.byref(plan), *_workspace_args(workspace),
         _stream_ptr(stream)),
@@ -403,12 +405,12 @@ class MaskOnlyLogits:
     def __init__(self, T, d, V, max_rows=None, budget_bytes=0, device="cuda", sampling=False):
         self.T, self.d, self.V = T, d, V
         self.max_rows = T if max_rows is None else max_rows
-        self.plan = mosaic_plan_workspace(T, self.max_rows, d, V, budget_bytes)
+        self.plan = mosaic_plan_workspace(T, self.max_rows, d, V, budget_bytes, sampling=sampling)
         dev = torch.device(device)
         self.idx = torch.empty(max(T, 1), dtype=torch.int32, device=dev)
         self.count = torch.zeros(1, dtype=torch.int32, device=dev)
         self.scratch = torch.empty(max(mosaic_compact_scratch_bytes(T), 16), dtype=torch.uint8, device=dev)
-        ws = mosaic_sample_workspace_bytes(self.plan) if sampling else self.plan.workspace_bytes
+        ws = self.plan.workspace_bytes          # sized by the selector for the decode mode, within the budget
         self.workspace = torch.empty(max(ws, 16), dtype=torch.uint8, device=dev)
         n = max(self.max_rows, 1)
         self.token = torch.empty(n, dtype=torch.int32, device=dev)

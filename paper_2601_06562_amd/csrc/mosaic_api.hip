@@ -38,7 +38,8 @@ int mosaic_mask_compact(const uint8_t* mask, int64_t T, int32_t* out_idx, int32_
 
 // Argument checks and launch shared by the greedy and the sampling entry points (temperature 0 = greedy).
 static int reduce_checked(const void* hidden, int64_t T, int32_t d, int64_t ld_h, const void* w, int32_t V,
-                          const int32_t* idx, const int32_t* count, int64_t max_rows, int32_t* out_token,
+                          const int32_t* idx, const int32_t* noise_idx, const int32_t* count, int64_t max_rows,
+                          int32_t* out_token,
                           float* out_conf, float* out_lse, const mosaic_plan* plan, void* workspace,
                           int64_t workspace_bytes, float temperature, uint64_t seed, void* stream) {
   if (T < 0 || d <= 0 || V < 0 || max_rows < 0 || max_rows > T || plan == nullptr || count == nullptr)
@@ -59,9 +60,11 @@ static int reduce_checked(const void* hidden, int64_t T, int32_t d, int64_t ld_h
       plan->vocab_splits < 1 || plan->vocab_splits > MOSAIC_MAX_VOCAB_SPLITS || plan->vocab_splits > vocab_tiles ||
       plan->tile_panel < 1 || plan->grid < 1 || (int64_t)plan->num_chunks * plan->rows_per_chunk < max_rows)
     return MOSAIC_ERR_INVALID_ARG;
-  const int64_t need = mosaic::partials_bytes(plan->rows_per_chunk, plan->vocab_splits);
-  if (plan->workspace_bytes < need || workspace_bytes < need) return MOSAIC_ERR_WORKSPACE_TOO_SMALL;
-  if (temperature > 0.f && workspace_bytes < mosaic::sample_partials_bytes(plan->rows_per_chunk, plan->vocab_splits))
+  // 12 bytes per row and split for a greedy pass, 20 for a sampling one -- whatever the plan was made for.
+  const int64_t need = temperature > 0.f ? mosaic::sample_partials_bytes(plan->rows_per_chunk, plan->vocab_splits)
+                                         : mosaic::partials_bytes(plan->rows_per_chunk, plan->vocab_splits);
+  if (workspace_bytes < need) return MOSAIC_ERR_WORKSPACE_TOO_SMALL;
+  if (plan->workspace_bytes < mosaic::partials_bytes(plan->rows_per_chunk, plan->vocab_splits))
     return MOSAIC_ERR_WORKSPACE_TOO_SMALL;
 
   mosaic::LogitsArgs a;
@@ -72,6 +75,7 @@ static int reduce_checked(const void* hidden, int64_t T, int32_t d, int64_t ld_h
   a.d = d;
   a.V = V;
   a.idx = idx;
+  a.noise_idx = noise_idx;
   a.count = count;
   a.max_rows = max_rows;
   a.out_token = out_token;
@@ -88,8 +92,8 @@ int mosaic_masked_logits_reduce(const void* hidden, int64_t T, int32_t d, int64_
                                 const int32_t* idx, const int32_t* count, int64_t max_rows, int32_t* out_token,
                                 float* out_conf, float* out_lse, const mosaic_plan* plan, void* workspace,
                                 int64_t workspace_bytes, void* stream) {
-  return reduce_checked(hidden, T, d, ld_h, w, V, idx, count, max_rows, out_token, out_conf, out_lse, plan, workspace,
-                        workspace_bytes, 0.f, 0, stream);
+  return reduce_checked(hidden, T, d, ld_h, w, V, idx, nullptr, count, max_rows, out_token, out_conf, out_lse, plan,
+                        workspace, workspace_bytes, 0.f, 0, stream);
 }
 
 int64_t mosaic_sample_workspace_bytes(const mosaic_plan* plan) {
@@ -98,12 +102,12 @@ int64_t mosaic_sample_workspace_bytes(const mosaic_plan* plan) {
 }
 
 int mosaic_masked_logits_sample(const void* hidden, int64_t T, int32_t d, int64_t ld_h, const void* w, int32_t V,
-                                const int32_t* idx, const int32_t* count, int64_t max_rows, float temperature,
-                                uint64_t seed, int32_t* out_token, float* out_conf, float* out_lse,
+                                const int32_t* idx, const int32_t* noise_idx, const int32_t* count, int64_t max_rows,
+                                float temperature, uint64_t seed, int32_t* out_token, float* out_conf, float* out_lse,
                                 const mosaic_plan* plan, void* workspace, int64_t workspace_bytes, void* stream) {
   if (!(temperature >= 0.f) || temperature > 1e30f) return MOSAIC_ERR_INVALID_ARG;   // also rejects NaN
-  return reduce_checked(hidden, T, d, ld_h, w, V, idx, count, max_rows, out_token, out_conf, out_lse, plan, workspace,
-                        workspace_bytes, temperature, seed, stream);
+  return reduce_checked(hidden, T, d, ld_h, w, V, idx, noise_idx, count, max_rows, out_token, out_conf, out_lse, plan,
+                        workspace, workspace_bytes, temperature, seed, stream);
 }
 
 int64_t mosaic_mfma_probe_flops(int32_t iters, int32_t num_wgs) {
@@ -130,7 +134,7 @@ int mosaic_unmask_topn(const float* conf, const int32_t* token, const int32_t* i
   if (conf == nullptr || token == nullptr || idx == nullptr || tokens == nullptr || mask == nullptr)
     return MOSAIC_ERR_INVALID_ARG;
   const int rc = mosaic::launch_unmask_topn(conf, token, idx, count, max_rows, seq_starts, num_seqs, n_per_seq, tokens,
-                                            mask, static_cast<hipStream_t>(stream));
+                                            mask, T, static_cast<hipStream_t>(stream));
   return rc == 0 ? MOSAIC_OK : MOSAIC_ERR_HIP;
 }
 

@@ -16,8 +16,7 @@ namespace mosaic {
 constexpr int kCompactThreads = 256;
 constexpr int kBytesPerThread = 16;
 constexpr int kCompactBlockElems = kCompactThreads * kBytesPerThread;  // 4096 positions per block
-
-int64_t compact_num_blocks(int64_t T) { return (T + kCompactBlockElems - 1) / kCompactBlockElems; }
+static_assert(kCompactBlockElems == kCompactBlockPositions, "the scratch size is computed from this constant");
 
 // Loads the 16 mask bytes a thread owns as a bit set (bit j = mask[base + j] != 0).
 __device__ __forceinline__ uint32_t load_flags(const uint8_t* __restrict__ mask, int64_t base, int64_t T,
@@ -150,21 +149,18 @@ __global__ __launch_bounds__(kSingleThreads) void compact_single_kernel(const ui
 int launch_compact(const uint8_t* mask, int64_t T, int32_t* out_idx, int32_t* out_count, int32_t* block_counts,
                    hipStream_t stream) {
   if (T <= kSingleMax) {
-    hipLaunchKernelGGL(compact_single_kernel, dim3(1), dim3(kSingleThreads), 0, stream, mask, T, out_idx, out_count);
-    return hipGetLastError() == hipSuccess ? 0 : -1;
+    return launch_kernel(compact_single_kernel, dim3(1), dim3(kSingleThreads), stream, mask, T, out_idx, out_count);
   }
   const int64_t nb = compact_num_blocks(T);
-  if (nb > 0) {
-    hipLaunchKernelGGL(compact_count_kernel, dim3((unsigned)nb), dim3(kCompactThreads), 0, stream, mask, T,
-                       block_counts);
-  }
+  int rc = 0;
+  if (nb > 0)
+    rc |= launch_kernel(compact_count_kernel, dim3((unsigned)nb), dim3(kCompactThreads), stream, mask, T, block_counts);
   // nb == 0 still has to publish count = 0.
-  hipLaunchKernelGGL(compact_scan_kernel, dim3(1), dim3(1024), 0, stream, block_counts, nb, out_count);
-  if (nb > 0) {
-    hipLaunchKernelGGL(compact_scatter_kernel, dim3((unsigned)nb), dim3(kCompactThreads), 0, stream, mask, T,
-                       block_counts, out_idx);
-  }
-  return hipGetLastError() == hipSuccess ? 0 : -1;
+  rc |= launch_kernel(compact_scan_kernel, dim3(1), dim3(1024), stream, block_counts, nb, out_count);
+  if (nb > 0)
+    rc |= launch_kernel(compact_scatter_kernel, dim3((unsigned)nb), dim3(kCompactThreads), stream, mask, T, block_counts,
+                        out_idx);
+  return rc;
 }
 
 }  // namespace mosaic

@@ -9,8 +9,20 @@
 
 namespace mosaic {
 
+// Enqueue a kernel and return THIS launch's status (0 / -1).  hipGetLastError() after a <<<>>> launch would also
+// report an error left behind by earlier, unrelated HIP calls of the host program.
+template <typename T>
+struct launch_arg { using type = T; };
+template <typename... P>
+inline int launch_kernel(void (*kernel)(P...), dim3 grid, dim3 block, hipStream_t stream,
+                         typename launch_arg<P>::type... args) {
+  void* argv[] = {const_cast<void*>(static_cast<const void*>(&args))...};
+  return hipLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, argv, 0, stream) == hipSuccess ? 0 : -1;
+}
+
 // ---- mask compaction (mosaic_compact.hip)
-int64_t compact_num_blocks(int64_t T);
+constexpr int kCompactBlockPositions = 4096;   // mask positions one block of the multi-block path counts and scatters
+inline int64_t compact_num_blocks(int64_t T) { return (T + kCompactBlockPositions - 1) / kCompactBlockPositions; }
 int launch_compact(const uint8_t* mask, int64_t T, int32_t* out_idx, int32_t* out_count, int32_t* block_counts,
                    hipStream_t stream);
 
@@ -22,7 +34,8 @@ struct LogitsArgs {
   const void* w;        // bf16 [V, d]
   int32_t d;
   int32_t V;
-  const int32_t* idx;   // masked positions, ascending
+  const int32_t* idx;   // hidden row to read per masked row (the masked positions themselves, or a shifted list)
+  const int32_t* noise_idx = nullptr;  // sampling: position that keys each row's noise; nullptr = idx
   const int32_t* count; // device scalar M
   int64_t max_rows;
   int32_t* out_token;
@@ -37,7 +50,7 @@ int launch_masked_logits(const LogitsArgs& a, const mosaic_plan& plan, hipStream
 // ---- sampling tail and shifted gather (mosaic_unmask.hip)
 int launch_unmask_topn(const float* conf, const int32_t* token, const int32_t* idx, const int32_t* count,
                        int64_t max_rows, const int32_t* seq_starts, int32_t num_seqs, const int32_t* n_per_seq,
-                       int32_t* tokens, uint8_t* mask, hipStream_t stream);
+                       int32_t* tokens, uint8_t* mask, int64_t T, hipStream_t stream);
 int launch_shift_indices(const int32_t* idx, const int32_t* count, int64_t max_rows, const int32_t* seq_starts,
                          int32_t num_seqs, int32_t* gather, hipStream_t stream);
 

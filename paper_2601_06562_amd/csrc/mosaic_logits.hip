@@ -58,8 +58,10 @@ struct KernelParams {
   const char* w;
   int32_t d;
   int32_t V;
-  const int32_t* idx;
+  const int32_t* idx;        // hidden row to read, per masked row
+  const int32_t* noise_idx;  // sampling: the position that keys the row's noise (idx unless the gather is shifted)
   const int32_t* count;
+  int32_t T;           // rows of hidden: gather entries are clamped to [0, T)
   int32_t row0;        // first compacted row of this chunk
   int32_t chunk_rows;  // capacity of the chunk (C)
   int32_t max_rows;
@@ -330,7 +332,8 @@ __global__ __launch_bounds__(kThreads) void masked_logits_kernel(const KernelPar
     for (int i = 0; i < 4; ++i) {
       int j = tt * kTileRows + drow + 8 * i;
       if (j > rows - 1) j = rows - 1;
-      const int t = p.idx[p.row0 + j];
+      int t = p.idx[p.row0 + j];
+      t = t < 0 ? 0 : (t > p.T - 1 ? p.T - 1 : t);   // a bad entry of a caller-built list reads a valid row
       hptr[i] = p.hidden + (int64_t)t * p.ldh_bytes + src_chunk_bytes[i];
     }
     const char* wptr[4];
@@ -392,7 +395,7 @@ __global__ __launch_bounds__(kThreads) void masked_logits_kernel(const KernelPar
       for (int bj = 0; bj < 2; ++bj) {
         int j = tt * kTileRows + wt * 64 + bj * 32 + l32;
         if (j > rows - 1) j = rows - 1;
-        pos[bj] = p.idx[p.row0 + j];
+        pos[bj] = p.noise_idx[p.row0 + j];
       }
     }
 
@@ -667,7 +670,8 @@ __global__ __launch_bounds__(256) void masked_logits_kernel_w4(const KernelParam
     for (int i = 0; i < 8; ++i) {
       int j = tt * kTileRows + drow + 8 * i;
       if (j > rows - 1) j = rows - 1;
-      const int t = p.idx[p.row0 + j];
+      int t = p.idx[p.row0 + j];
+      t = t < 0 ? 0 : (t > p.T - 1 ? p.T - 1 : t);   // a bad entry of a caller-built list reads a valid row
       hoff[i] = (uint32_t)t * (uint32_t)p.ldh_bytes + ((i & 1) ? chunk_odd : chunk_even);
     }
 
@@ -716,7 +720,7 @@ __global__ __launch_bounds__(256) void masked_logits_kernel_w4(const KernelParam
       if constexpr (SAMPLE) {   // the position whose row this lane's column tb holds
         int j = tt * kTileRows + wt * 128 + tb * 16 + l16;
         if (j > rows - 1) j = rows - 1;
-        pos[tb] = p.idx[p.row0 + j];
+        pos[tb] = p.noise_idx[p.row0 + j];
       }
     }
 
@@ -867,7 +871,9 @@ int launch_masked_logits(const LogitsArgs& a, const mosaic_plan& plan, hipStream
   p.d = a.d;
   p.V = a.V;
   p.idx = a.idx;
+  p.noise_idx = a.noise_idx != nullptr ? a.noise_idx : a.idx;
   p.count = a.count;
+  p.T = (int32_t)a.T;
   p.chunk_rows = plan.rows_per_chunk;
   p.max_rows = (int32_t)a.max_rows;
   p.splits = plan.vocab_splits;
@@ -912,6 +918,7 @@ int launch_masked_logits(const LogitsArgs& a, const mosaic_plan& plan, hipStream
     tail.split_first = body.splits;
     p.splits = body.splits + 1;        // what the merge reads
   }
+  int rc = 0;
   for (int c = 0; c < plan.num_chunks; ++c) {
     const int64_t row0 = (int64_t)c * plan.rows_per_chunk;
     if (row0 >= a.max_rows) break;
@@ -923,23 +930,24 @@ int launch_masked_logits(const LogitsArgs& a, const mosaic_plan& plan, hipStream
     int64_t grid = tiles * q.splits;
     if (grid > plan.grid) grid = plan.grid;
     if ((fast || paired) && sample)
-      hipLaunchKernelGGL((masked_logits_kernel_w4<true>), dim3((unsigned)grid), dim3(256), 0, stream, q);
+      rc |= launch_kernel(masked_logits_kernel_w4<true>, dim3((unsigned)grid), dim3(256), stream, q);
     else if (fast || paired)
-      hipLaunchKernelGGL((masked_logits_kernel_w4<false>), dim3((unsigned)grid), dim3(256), 0, stream, q);
+      rc |= launch_kernel(masked_logits_kernel_w4<false>, dim3((unsigned)grid), dim3(256), stream, q);
     else if (sample)
-      hipLaunchKernelGGL((masked_logits_kernel<3, 2, true>), dim3((unsigned)grid), dim3(kThreads), 0, stream, p);
+      rc |= launch_kernel(masked_logits_kernel<3, 2, true>, dim3((unsigned)grid), dim3(kThreads), stream, p);
     else
-      hipLaunchKernelGGL((masked_logits_kernel<3, 2, false>), dim3((unsigned)grid), dim3(kThreads), 0, stream, p);
+      rc |= launch_kernel(masked_logits_kernel<3, 2, false>, dim3((unsigned)grid), dim3(kThreads), stream, p);
     if (paired) {
       const int64_t tgrid = tiles < plan.grid ? tiles : plan.grid;
       if (sample)
-        hipLaunchKernelGGL((masked_logits_kernel<3, 2, true>), dim3((unsigned)tgrid), dim3(kThreads), 0, stream, tail);
+        rc |= launch_kernel(masked_logits_kernel<3, 2, true>, dim3((unsigned)tgrid), dim3(kThreads), stream, tail);
       else
-        hipLaunchKernelGGL((masked_logits_kernel<3, 2, false>), dim3((unsigned)tgrid), dim3(kThreads), 0, stream, tail);
+        rc |= launch_kernel(masked_logits_kernel<3, 2, false>, dim3((unsigned)tgrid), dim3(kThreads), stream, tail);
     }
-    hipLaunchKernelGGL(combine_kernel, dim3((unsigned)((cap + kCombineRows - 1) / kCombineRows)), dim3(256), 0, stream, p);
+    rc |= launch_kernel(combine_kernel, dim3((unsigned)((cap + kCombineRows - 1) / kCombineRows)), dim3(256), stream, p);
+    if (rc != 0) break;
   }
-  return hipGetLastError() == hipSuccess ? 0 : -1;
+  return rc;
 }
 
 }  // namespace mosaic

@@ -5,7 +5,8 @@
 // the operator that forms the peak by one, re-evaluates the footprint, and stops at the first
 // configuration that fits, or fails when only non-chunkable memory is left.  On this path the one
 // chunkable buffer is the array of partial (max, sum-exp, arg-max) triples, 12 bytes per row and
-// vocabulary split; its non-chunkable floor is one row tile with one split.
+// vocabulary split (20 when the step samples with a temperature: two more values per partial); its
+// non-chunkable floor is one row tile with one split.
 #include <stdint.h>
 
 #include "mosaic_internal.h"
@@ -44,9 +45,10 @@ int32_t choose_vocab_splits(int64_t row_tiles, int64_t vocab_tiles, int32_t num_
 }  // namespace mosaic
 
 extern "C" int mosaic_plan_workspace(int64_t T, int64_t max_rows, int32_t d, int32_t V, int64_t budget_bytes,
-                                     int32_t num_cus, mosaic_plan* out_plan) {
+                                     int32_t num_cus, int32_t sampling, mosaic_plan* out_plan) {
   using namespace mosaic;
-  if (out_plan == nullptr || T < 0 || max_rows < 0 || max_rows > T || d <= 0 || V < 0) return MOSAIC_ERR_INVALID_ARG;
+  if (out_plan == nullptr || T < 0 || max_rows < 0 || max_rows > T || d <= 0 || V < 0 || (sampling != 0 && sampling != 1))
+    return MOSAIC_ERR_INVALID_ARG;
   if (T >= (int64_t)1 << 31 || (int64_t)V >= ((int64_t)1 << 31) - MOSAIC_VOCAB_TILE || d % MOSAIC_K_TILE != 0)
     return MOSAIC_ERR_UNSUPPORTED_SHAPE;
   if (num_cus <= 0) num_cus = 256;
@@ -64,11 +66,12 @@ extern "C" int mosaic_plan_workspace(int64_t T, int64_t max_rows, int32_t d, int
                        : choose_vocab_splits(row_tiles, vocab_tiles, num_cus);
     if (S > MOSAIC_MAX_VOCAB_SPLITS) S = MOSAIC_MAX_VOCAB_SPLITS;
     if (budget_bytes > 0) {
-      const int64_t fit = budget_bytes / partials_bytes(C, 1);  // splits the budget allows
+      // splits the budget allows (a sampling step keeps 20 bytes per row and split, a greedy one 12)
+      const int64_t fit = budget_bytes / (sampling ? sample_partials_bytes(C, 1) : partials_bytes(C, 1));
       if (fit < S) S = fit;
     }
     if (S >= 1) {
-      out_plan->workspace_bytes = partials_bytes(C, (int32_t)S);
+      out_plan->workspace_bytes = sampling ? sample_partials_bytes(C, (int32_t)S) : partials_bytes(C, (int32_t)S);
       out_plan->num_chunks = (int32_t)((rows + C - 1) / C);  // chunks that actually hold rows
       out_plan->rows_per_chunk = (int32_t)C;
       out_plan->vocab_splits = (int32_t)S;
@@ -76,7 +79,7 @@ extern "C" int mosaic_plan_workspace(int64_t T, int64_t max_rows, int32_t d, int
       int64_t grid = row_tiles * S;
       if (grid > num_cus) grid = num_cus;
       out_plan->grid = (int32_t)grid;
-      out_plan->flags = 0;
+      out_plan->flags = sampling ? MOSAIC_PLAN_SAMPLING : 0;
       return MOSAIC_OK;
     }
     if (C == MOSAIC_ROW_TILE) return MOSAIC_ERR_WORKSPACE_TOO_SMALL;  // nothing left to chunk

@@ -42,9 +42,8 @@ __global__ __launch_bounds__(256) void mfma_probe_kernel(const bf16x8* __restric
 }  // namespace
 
 int launch_mfma_probe(const void* operands, float* sink, int32_t iters, int32_t num_wgs, hipStream_t stream) {
-  hipLaunchKernelGGL(mfma_probe_kernel, dim3((unsigned)num_wgs), dim3(256), 0, stream,
-                     static_cast<const bf16x8*>(operands), sink, (int)iters);
-  return hipGetLastError() == hipSuccess ? 0 : -1;
+  return launch_kernel(mfma_probe_kernel, dim3((unsigned)num_wgs), dim3(256), stream,
+                       static_cast<const bf16x8*>(operands), sink, (int)iters);
 }
 
 }  // namespace mosaic

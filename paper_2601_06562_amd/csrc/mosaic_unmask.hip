@@ -45,7 +45,7 @@ __device__ __forceinline__ int block_exclusive_scan_flag(int flag, int* wave_tot
 __global__ __launch_bounds__(kUnmaskThreads) void unmask_topn_kernel(
     const float* __restrict__ conf, const int32_t* __restrict__ token, const int32_t* __restrict__ idx,
     const int32_t* __restrict__ count, int32_t max_rows, const int32_t* __restrict__ seq_starts,
-    const int32_t* __restrict__ n_per_seq, int32_t* __restrict__ tokens, uint8_t* __restrict__ mask) {
+    const int32_t* __restrict__ n_per_seq, int32_t* __restrict__ tokens, uint8_t* __restrict__ mask, int32_t T) {
   __shared__ int hist[256];
   __shared__ int wave_tot[kUnmaskThreads / 64];
   __shared__ uint32_t sh_prefix;
@@ -103,8 +103,10 @@ __global__ __launch_bounds__(kUnmaskThreads) void unmask_topn_kernel(
     const bool take = valid && (all || k > prefix || (eq && rank < need));
     if (take) {
       const int t = idx[j];
-      tokens[t] = token[j];
-      mask[t] = 0;
+      if (t >= 0 && t < T) {   // an entry outside [0, T) of a caller-built list is skipped, never written through
+        tokens[t] = token[j];
+        mask[t] = 0;
+      }
     }
   }
 }
@@ -124,22 +126,23 @@ __global__ __launch_bounds__(256) void shift_indices_kernel(const int32_t* __res
     const int mid = (lo + hi) >> 1;
     if (seq_starts[mid] <= pos) lo = mid; else hi = mid;
   }
-  gather[j] = (seq_starts[lo] == pos) ? pos : pos - 1;
+  int g = (seq_starts[lo] == pos) ? pos : pos - 1;
+  const int last = seq_starts[num_seqs] - 1;   // T - 1: an out-of-range entry is clamped, never passed on
+  g = g > last ? last : g;
+  gather[j] = g < 0 ? 0 : g;
 }
 
 int launch_unmask_topn(const float* conf, const int32_t* token, const int32_t* idx, const int32_t* count,
                        int64_t max_rows, const int32_t* seq_starts, int32_t num_seqs, const int32_t* n_per_seq,
-                       int32_t* tokens, uint8_t* mask, hipStream_t stream) {
-  hipLaunchKernelGGL(unmask_topn_kernel, dim3((unsigned)num_seqs), dim3(kUnmaskThreads), 0, stream, conf, token, idx,
-                     count, (int32_t)max_rows, seq_starts, n_per_seq, tokens, mask);
-  return hipGetLastError() == hipSuccess ? 0 : -1;
+                       int32_t* tokens, uint8_t* mask, int64_t T, hipStream_t stream) {
+  return launch_kernel(unmask_topn_kernel, dim3((unsigned)num_seqs), dim3(kUnmaskThreads), stream, conf, token, idx,
+                       count, (int32_t)max_rows, seq_starts, n_per_seq, tokens, mask, (int32_t)T);
 }
 
 int launch_shift_indices(const int32_t* idx, const int32_t* count, int64_t max_rows, const int32_t* seq_starts,
                          int32_t num_seqs, int32_t* gather, hipStream_t stream) {
-  hipLaunchKernelGGL(shift_indices_kernel, dim3((unsigned)((max_rows + 255) / 256)), dim3(256), 0, stream, idx, count,
-                     (int32_t)max_rows, seq_starts, num_seqs, gather);
-  return hipGetLastError() == hipSuccess ? 0 : -1;
+  return launch_kernel(shift_indices_kernel, dim3((unsigned)((max_rows + 255) / 256)), dim3(256), stream, idx, count,
+                       (int32_t)max_rows, seq_starts, num_seqs, gather);
 }
 
 }  // namespace mosaic

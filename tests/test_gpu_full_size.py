@@ -150,16 +150,16 @@ def test_dream_shape_shifted_prediction_and_sampling():
     stats = check_against_oracle(dict(tok=op.token[:M].cpu().numpy()[rows], conf=op.conf[:M].cpu().numpy()[rows],
                                       lse=op.lse[:M].cpu().numpy()[rows]), want, logits, what=name + " shifted")
     print(f"{name} shifted: {stats}", flush=True)
-    # the same gather list under sampling: the noise is keyed by the row that is READ (the entry of the list)
+    # the same gather list under sampling: the noise is keyed by the position that is PREDICTED (noise_idx)
     tau, seed = 0.7, 20260107
     binding.mosaic_masked_logits_sample(wl.hidden, wl.w, gather, op.count, op.max_rows, tau, seed, op.token, op.conf,
-                                        op.lse, op.plan, op.workspace)
+                                        op.lse, op.plan, op.workspace, noise_idx=op.idx)
     torch.cuda.synchronize()
     tok, conf, lse = op.token[:M].cpu().numpy(), op.conf[:M].cpu().numpy(), op.lse[:M].cpu().numpy()
     strict = 0
     for k, j in enumerate(rows):
         x = logits[k]
-        tok_o, conf_o, lse_o, gap_o = oracle.row_sample(x, tau, seed, int(rows_read[j]))
+        tok_o, conf_o, lse_o, gap_o = oracle.row_sample(x, tau, seed, int(idx[j]))
         assert abs(float(lse[j]) - lse_o) <= 2e-3
         if gap_o > 1e-3 * (1 + tau):
             strict += 1

@@ -29,16 +29,16 @@ def test_library_exports_every_declared_symbol():
     assert binding.status_string(-3) == "MOSAIC_ERR_WORKSPACE_TOO_SMALL"
 
 
-def workspace(C, S):
-    return 12 * C * S
+def workspace(C, S, per_partial=12):
+    return per_partial * C * S
 
 
-def brute_force_min_chunks(max_rows, budget):
+def brute_force_min_chunks(max_rows, budget, per_partial=12):
     """Smallest K whose chunk fits with a single split, by enumeration (section 4.4: minimal K)."""
     rows = max(max_rows, 1)
     for K in range(1, rows + 1):
         C = -(-(-(-rows // K)) // 256) * 256
-        if workspace(C, 1) <= budget:
+        if workspace(C, 1, per_partial) <= budget:
             return K, C
     return None
 
@@ -65,6 +65,33 @@ def test_selector_matches_brute_force(rows, budget):
     assert roomy.num_chunks <= plan.num_chunks
 
 
+@pytest.mark.parametrize("rows", [300, 4096, 5000, 58491])
+@pytest.mark.parametrize("budget", [5120, 5121, 20 * 256 * 7, 12 * 4096, 20 * 4096, 100000, 10 ** 6])
+def test_selector_bounds_the_sampling_workspace(rows, budget):
+    """A plan for a sampling step keeps 20 bytes per row and split; the budget bounds THAT (section 4.4: the search
+    stops only at a configuration that fits), with the same minimal-K rule."""
+    plan = binding.mosaic_plan_workspace(131072, rows, 4096, 126464, budget, sampling=True)
+    assert plan.flags & binding.PLAN_SAMPLING
+    K, C = brute_force_min_chunks(rows, budget, per_partial=20)
+    assert plan.rows_per_chunk == C and plan.num_chunks == -(-rows // C)
+    assert plan.workspace_bytes == 20 * plan.rows_per_chunk * plan.vocab_splits <= budget
+    assert binding.mosaic_sample_workspace_bytes(plan) == plan.workspace_bytes
+    greedy = binding.mosaic_plan_workspace(131072, rows, 4096, 126464, budget)
+    assert not greedy.flags & binding.PLAN_SAMPLING and greedy.num_chunks <= plan.num_chunks
+    assert greedy.workspace_bytes == 12 * greedy.rows_per_chunk * greedy.vocab_splits <= budget
+
+
+def test_sampling_selector_floor_and_unbounded_size():
+    with pytest.raises(binding.MosaicError) as e:
+        binding.mosaic_plan_workspace(4096, 4096, 4096, 126464, 5119, sampling=True)      # 20 * 256 - 1
+    assert e.value.status == binding.MOSAIC_ERR_WORKSPACE_TOO_SMALL
+    assert binding.mosaic_plan_workspace(4096, 4096, 4096, 126464, 5120, sampling=True).rows_per_chunk == 256
+    a = binding.mosaic_plan_workspace(4096, 4096, 4096, 126464, 0)
+    b = binding.mosaic_plan_workspace(4096, 4096, 4096, 126464, 0, sampling=True)
+    assert (a.num_chunks, a.rows_per_chunk, a.vocab_splits, a.grid) == (b.num_chunks, b.rows_per_chunk, b.vocab_splits, b.grid)
+    assert b.workspace_bytes * 12 == a.workspace_bytes * 20
+
+
 def test_selector_failure_is_exactly_the_non_chunkable_floor():
     with pytest.raises(binding.MosaicError) as e:
         binding.mosaic_plan_workspace(4096, 4096, 4096, 126464, 3071)
@@ -85,12 +112,14 @@ def test_selector_rejects_bad_arguments():
     L = binding.lib()
     plan = MosaicPlan()
     ok = lambda *a: L.mosaic_plan_workspace(*a, ctypes.byref(plan))
-    assert ok(-1, 0, 4096, 1000, 0, 0) == binding.MOSAIC_ERR_INVALID_ARG
-    assert ok(10, 11, 4096, 1000, 0, 0) == binding.MOSAIC_ERR_INVALID_ARG
-    assert ok(10, 10, 4000, 1000, 0, 0) == binding.MOSAIC_ERR_UNSUPPORTED_SHAPE
-    assert ok(2 ** 31, 10, 4096, 1000, 0, 0) == binding.MOSAIC_ERR_UNSUPPORTED_SHAPE
-    assert L.mosaic_plan_workspace(10, 10, 4096, 1000, 0, 0, None) == binding.MOSAIC_ERR_INVALID_ARG
-    assert ok(0, 0, 64, 1, 0, 0) == binding.MOSAIC_OK
+    assert ok(-1, 0, 4096, 1000, 0, 0, 0) == binding.MOSAIC_ERR_INVALID_ARG
+    assert ok(10, 11, 4096, 1000, 0, 0, 0) == binding.MOSAIC_ERR_INVALID_ARG
+    assert ok(10, 10, 4000, 1000, 0, 0, 0) == binding.MOSAIC_ERR_UNSUPPORTED_SHAPE
+    assert ok(2 ** 31, 10, 4096, 1000, 0, 0, 0) == binding.MOSAIC_ERR_UNSUPPORTED_SHAPE
+    assert L.mosaic_plan_workspace(10, 10, 4096, 1000, 0, 0, 0, None) == binding.MOSAIC_ERR_INVALID_ARG
+    assert ok(10, 10, 4096, 1000, 0, 0, 2) == binding.MOSAIC_ERR_INVALID_ARG            # decode mode is 0 or 1
+    assert ok(10, 10, 4096, 1000, 0, 0, -1) == binding.MOSAIC_ERR_INVALID_ARG
+    assert ok(0, 0, 64, 1, 0, 0, 0) == binding.MOSAIC_OK and ok(0, 0, 64, 1, 0, 0, 1) == binding.MOSAIC_OK
 
 
 def test_entry_points_validate_before_launch():
@@ -156,9 +185,9 @@ def test_sampling_entry_point_validates_before_launch():
     assert need > plan.workspace_bytes
     assert L.mosaic_sample_workspace_bytes(None) == 0
     call = lambda **kw: L.mosaic_masked_logits_sample(
-        kw.get("hidden", fake), 4096, kw.get("d", 4096), 4096, fake, 126464, fake, kw.get("count", fake),
-        kw.get("max_rows", 4096), kw.get("tau", 1.0), kw.get("seed", 7), fake, fake, fake, ctypes.byref(plan), fake,
-        kw.get("ws_bytes", need), null)
+        kw.get("hidden", fake), 4096, kw.get("d", 4096), 4096, fake, 126464, fake, kw.get("noise_idx", null),
+        kw.get("count", fake), kw.get("max_rows", 4096), kw.get("tau", 1.0), kw.get("seed", 7), fake, fake, fake,
+        ctypes.byref(plan), fake, kw.get("ws_bytes", need), null)
     assert call(tau=-0.5) == binding.MOSAIC_ERR_INVALID_ARG
     assert call(tau=float("nan")) == binding.MOSAIC_ERR_INVALID_ARG
     assert call(tau=float("inf")) == binding.MOSAIC_ERR_INVALID_ARG
@@ -168,6 +197,7 @@ def test_sampling_entry_point_validates_before_launch():
     assert call(count=null) == binding.MOSAIC_ERR_INVALID_ARG
     assert call(d=4090) == binding.MOSAIC_ERR_UNSUPPORTED_SHAPE
     assert call(max_rows=0) == binding.MOSAIC_OK                                   # nothing to do
+    assert call(max_rows=0, noise_idx=fake) == binding.MOSAIC_OK                   # the optional list is accepted
     assert call(seed=2 ** 64 - 1, tau=-1.0) == binding.MOSAIC_ERR_INVALID_ARG      # a full 64-bit seed is accepted
 
 
