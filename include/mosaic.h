@@ -152,6 +152,28 @@ int mosaic_masked_logits_reduce(const void *hidden, int64_t T, int32_t d, int64_
                                 int64_t workspace_bytes, void *stream);
 
 /*
+ * mosaic_masked_logits_reduce for callers that cannot allocate device memory or hand in a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and
+ * errors as mosaic_masked_logits_reduce, except that the partial results go to a fixed array of
+ * MOSAIC_STATIC_WORKSPACE_BYTES inside the library's device image instead of a caller's `workspace`; the call
+ * itself allocates and frees nothing.
+ *   plan   must need at most MOSAIC_STATIC_WORKSPACE_BYTES (12 * rows_per_chunk * vocab_splits bytes), else
+ *          MOSAIC_ERR_WORKSPACE_TOO_SMALL and nothing is enqueued: make the plan with
+ *          budget_bytes = MOSAIC_STATIC_WORKSPACE_BYTES and the selector chunks the rows to fit
+ * Every GPU the library runs on holds one copy of the array until the process ends, and every call on a GPU uses
+ * that GPU's copy (the current device of the calling thread, which must be `stream`'s): calls that overlap on
+ * one GPU -- different streams, or a captured graph replayed while another call runs -- race on it; calls in
+ * one stream are ordered and safe.  Nothing in the array needs to start at zero (every partial that is read has
+ * been written by the same call).  The first call on a device looks the array's address up (one
+ * hipGetSymbolAddress, which may load the library's device image): make it before a capture begins.
+ */
+#define MOSAIC_STATIC_WORKSPACE_BYTES (4 << 20)
+int mosaic_masked_logits_reduce_static(const void *hidden, int64_t T, int32_t d, int64_t ld_h, const void *w, int32_t V,
+                                       const int32_t *idx, const int32_t *count, int64_t max_rows,
+                                       int32_t *out_token, float *out_conf, float *out_lse, const mosaic_plan *plan,
+                                       void *stream);
+
+/*
  * The same fused pass with temperature sampling in place of the arg-max (paper section 2.1: tokens are
  * sampled from the logits; the paper fixes no sampler -- the reading here is the Gumbel-max form of
  * categorical sampling at temperature tau, which draws v with probability softmax(x / tau)[v] and needs

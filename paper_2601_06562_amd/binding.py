@@ -25,10 +25,12 @@ VOCAB_TILE = 256
 K_TILE = 64
 PLAN_GENERAL_KERNEL = 1   # plan.flags bit: force the general 8-wave kernel
 PLAN_SAMPLING = 2         # plan.flags bit: sized for a sampling step (20 bytes per partial)
+STATIC_WORKSPACE_BYTES = 4 << 20   # the fixed array behind mosaic_masked_logits_reduce_static
 
 EXPORTS = (
     "mosaic_status_string", "mosaic_plan_workspace", "mosaic_compact_scratch_bytes", "mosaic_mask_compact",
-    "mosaic_masked_logits_reduce", "mosaic_sample_workspace_bytes", "mosaic_masked_logits_sample",
+    "mosaic_masked_logits_reduce", "mosaic_masked_logits_reduce_static", "mosaic_sample_workspace_bytes",
+    "mosaic_masked_logits_sample",
     "mosaic_unmask_topn", "mosaic_shift_indices", "mosaic_mfma_probe_flops", "mosaic_mfma_probe", "mosaic_version",
     "mosaic_vmm_create", "mosaic_vmm_resize", "mosaic_vmm_ptr", "mosaic_vmm_committed_bytes",
     "mosaic_vmm_reserved_bytes", "mosaic_vmm_granularity", "mosaic_vmm_last_error", "mosaic_vmm_destroy",
@@ -98,6 +100,9 @@ def lib():
         L.mosaic_masked_logits_reduce.restype = ctypes.c_int
         L.mosaic_masked_logits_reduce.argtypes = [p, i64, i32, i64, p, i32, p, p, i64, p, p, p,
                                                   ctypes.POINTER(MosaicPlan), p, i64, p]
+        L.mosaic_masked_logits_reduce_static.restype = ctypes.c_int
+        L.mosaic_masked_logits_reduce_static.argtypes = [p, i64, i32, i64, p, i32, p, p, i64, p, p, p,
+                                                         ctypes.POINTER(MosaicPlan), p]
         L.mosaic_sample_workspace_bytes.restype = i64
         L.mosaic_sample_workspace_bytes.argtypes = [ctypes.POINTER(MosaicPlan)]
         L.mosaic_masked_logits_sample.restype = ctypes.c_int
@@ -222,6 +227,23 @@ def mosaic_masked_logits_reduce(hidden, w, idx, count, max_rows, out_token, out_
         _dev_ptr(out_lse, "out_lse", torch.float32), ctypes.byref(plan), *_workspace_args(workspace),
         _stream_ptr(stream)),
         "mosaic_masked_logits_reduce")
+
+
+def mosaic_masked_logits_reduce_static(hidden, w, idx, count, max_rows, out_token, out_conf, out_lse, plan, stream=None):
+    """mosaic_masked_logits_reduce on the library's own fixed workspace (allocates nothing)."""
+    T, d = hidden.shape
+    V, d2 = w.shape
+    if d != d2:
+        raise ValueError("hidden and w disagree on d")
+    if hidden.stride(1) != 1 or not w.is_contiguous():
+        raise ValueError("hidden rows and w must be dense along d")
+    ld_h = hidden.stride(0) if T > 1 else d
+    _check(lib().mosaic_masked_logits_reduce_static(
+        _dev_ptr(hidden, "hidden", torch.bfloat16), T, d, ld_h, _dev_ptr(w, "w", torch.bfloat16), V,
+        _dev_ptr(idx, "idx", torch.int32), _dev_ptr(count, "count", torch.int32), max_rows,
+        _dev_ptr(out_token, "out_token", torch.int32), _dev_ptr(out_conf, "out_conf", torch.float32),
+        _dev_ptr(out_lse, "out_lse", torch.float32), ctypes.byref(plan), _stream_ptr(stream)),
+        "mosaic_masked_logits_reduce_static")
 
 
 def mosaic_sample_workspace_bytes(plan) -> int:

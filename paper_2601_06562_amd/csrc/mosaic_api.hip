@@ -2,7 +2,35 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "mosaic_internal.h"
+
+// Workspace of mosaic_masked_logits_reduce_static, the entry point for callers that cannot allocate: a fixed
+// array in the library's own device image.  Each GPU the library runs on holds its own copy, at its own address,
+// until the process ends.  The name is a host-side stand-in, not a device address: host code only ever uses the
+// pointer that hipGetSymbolAddress returns for the current device (static_scratch below).
+static __device__ __align__(256) unsigned char scratch[MOSAIC_STATIC_WORKSPACE_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices];   // resolved once per device, on that device's first call
+
+// Device address of `scratch` on the calling thread's current device.
+int static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return MOSAIC_ERR_HIP;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return MOSAIC_ERR_HIP;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return MOSAIC_OK;
+}
+}  // namespace
 
 extern "C" {
 
@@ -41,7 +69,8 @@ static int reduce_checked(const void* hidden, int64_t T, int32_t d, int64_t ld_h
                           const int32_t* idx, const int32_t* noise_idx, const int32_t* count, int64_t max_rows,
                           int32_t* out_token,
                           float* out_conf, float* out_lse, const mosaic_plan* plan, void* workspace,
-                          int64_t workspace_bytes, float temperature, uint64_t seed, void* stream) {
+                          int64_t workspace_bytes, bool static_workspace, float temperature, uint64_t seed,
+                          void* stream) {
   if (T < 0 || d <= 0 || V < 0 || max_rows < 0 || max_rows > T || plan == nullptr || count == nullptr)
     return MOSAIC_ERR_INVALID_ARG;
   if (T >= (int64_t)1 << 31 || (int64_t)V >= ((int64_t)1 << 31) - MOSAIC_VOCAB_TILE || d % MOSAIC_K_TILE != 0 ||
@@ -49,7 +78,7 @@ static int reduce_checked(const void* hidden, int64_t T, int32_t d, int64_t ld_h
     return MOSAIC_ERR_UNSUPPORTED_SHAPE;
   if (max_rows == 0 || V == 0) return MOSAIC_OK;
   if (hidden == nullptr || w == nullptr || idx == nullptr || out_token == nullptr || out_conf == nullptr ||
-      out_lse == nullptr || workspace == nullptr)
+      out_lse == nullptr || (workspace == nullptr && !static_workspace))
     return MOSAIC_ERR_INVALID_ARG;
   if ((reinterpret_cast<uintptr_t>(hidden) & 15u) || (reinterpret_cast<uintptr_t>(w) & 15u) ||
       (reinterpret_cast<uintptr_t>(workspace) & 15u))
@@ -63,9 +92,15 @@ static int reduce_checked(const void* hidden, int64_t T, int32_t d, int64_t ld_h
   // 12 bytes per row and split for a greedy pass, 20 for a sampling one -- whatever the plan was made for.
   const int64_t need = temperature > 0.f ? mosaic::sample_partials_bytes(plan->rows_per_chunk, plan->vocab_splits)
                                          : mosaic::partials_bytes(plan->rows_per_chunk, plan->vocab_splits);
-  if (workspace_bytes < need) return MOSAIC_ERR_WORKSPACE_TOO_SMALL;
   if (plan->workspace_bytes < mosaic::partials_bytes(plan->rows_per_chunk, plan->vocab_splits))
     return MOSAIC_ERR_WORKSPACE_TOO_SMALL;
+  if (static_workspace) {   // the library's own fixed array: the plan must fit it, nothing is allocated
+    if (need > MOSAIC_STATIC_WORKSPACE_BYTES) return MOSAIC_ERR_WORKSPACE_TOO_SMALL;
+    const int rc = static_scratch(&workspace);
+    if (rc != MOSAIC_OK) return rc;
+    workspace_bytes = MOSAIC_STATIC_WORKSPACE_BYTES;
+  }
+  if (workspace_bytes < need) return MOSAIC_ERR_WORKSPACE_TOO_SMALL;
 
   mosaic::LogitsArgs a;
   a.hidden = hidden;
@@ -93,7 +128,14 @@ int mosaic_masked_logits_reduce(const void* hidden, int64_t T, int32_t d, int64_
                                 float* out_conf, float* out_lse, const mosaic_plan* plan, void* workspace,
                                 int64_t workspace_bytes, void* stream) {
   return reduce_checked(hidden, T, d, ld_h, w, V, idx, nullptr, count, max_rows, out_token, out_conf, out_lse, plan,
-                        workspace, workspace_bytes, 0.f, 0, stream);
+                        workspace, workspace_bytes, false, 0.f, 0, stream);
+}
+
+int mosaic_masked_logits_reduce_static(const void* hidden, int64_t T, int32_t d, int64_t ld_h, const void* w, int32_t V,
+                                       const int32_t* idx, const int32_t* count, int64_t max_rows, int32_t* out_token,
+                                       float* out_conf, float* out_lse, const mosaic_plan* plan, void* stream) {
+  return reduce_checked(hidden, T, d, ld_h, w, V, idx, nullptr, count, max_rows, out_token, out_conf, out_lse, plan,
+                        nullptr, 0, true, 0.f, 0, stream);
 }
 
 int64_t mosaic_sample_workspace_bytes(const mosaic_plan* plan) {
@@ -107,7 +149,7 @@ int mosaic_masked_logits_sample(const void* hidden, int64_t T, int32_t d, int64_
                                 const mosaic_plan* plan, void* workspace, int64_t workspace_bytes, void* stream) {
   if (!(temperature >= 0.f) || temperature > 1e30f) return MOSAIC_ERR_INVALID_ARG;   // also rejects NaN
   return reduce_checked(hidden, T, d, ld_h, w, V, idx, noise_idx, count, max_rows, out_token, out_conf, out_lse, plan,
-                        workspace, workspace_bytes, temperature, seed, stream);
+                        workspace, workspace_bytes, false, temperature, seed, stream);
 }
 
 int64_t mosaic_mfma_probe_flops(int32_t iters, int32_t num_wgs) {

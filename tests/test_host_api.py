@@ -153,6 +153,30 @@ def test_entry_points_validate_before_launch():
     assert call(plan=ctypes.byref(small), ws_bytes=1 << 30) == binding.MOSAIC_ERR_INVALID_ARG
 
 
+def test_static_workspace_entry_point_validates_before_touching_the_device():
+    L = binding.lib()
+    null, fake = ctypes.c_void_p(0), ctypes.c_void_p(0x1000)
+    plan = binding.mosaic_plan_workspace(4096, 4096, 4096, 126464, 0)
+    assert plan.workspace_bytes <= binding.STATIC_WORKSPACE_BYTES
+    call = lambda **kw: L.mosaic_masked_logits_reduce_static(
+        kw.get("hidden", fake), kw.get("T", 4096), kw.get("d", 4096), 4096, fake, 126464, fake, kw.get("count", fake),
+        kw.get("max_rows", 4096), fake, fake, fake, kw.get("plan", ctypes.byref(plan)), null)
+    assert call(hidden=null) == binding.MOSAIC_ERR_INVALID_ARG
+    assert call(count=null) == binding.MOSAIC_ERR_INVALID_ARG
+    assert call(d=4090) == binding.MOSAIC_ERR_UNSUPPORTED_SHAPE
+    assert call(max_rows=0) == binding.MOSAIC_OK
+    # a plan beyond the fixed array is refused with a clear status, before any device call
+    big = binding.mosaic_plan_workspace(131072, 58501, 4096, 126464, 0)
+    assert big.workspace_bytes > binding.STATIC_WORKSPACE_BYTES
+    assert L.mosaic_masked_logits_reduce_static(fake, 131072, 4096, 4096, fake, 126464, fake, fake, 58501, fake, fake,
+                                                fake, ctypes.byref(big), null) == binding.MOSAIC_ERR_WORKSPACE_TOO_SMALL
+    # ... and the selector, given the array's size as the budget, chunks the same rows to fit
+    fits = binding.mosaic_plan_workspace(131072, 58501, 4096, 126464, binding.STATIC_WORKSPACE_BYTES)
+    assert fits.workspace_bytes <= binding.STATIC_WORKSPACE_BYTES
+    header = open(os.path.join(ROOT, "include", "mosaic.h")).read()
+    assert "#define MOSAIC_STATIC_WORKSPACE_BYTES (4 << 20)" in header and binding.STATIC_WORKSPACE_BYTES == 4 << 20
+
+
 def test_sampling_tail_entry_points_validate_before_launch():
     L = binding.lib()
     null, fake = ctypes.c_void_p(0), ctypes.c_void_p(0x1000)
