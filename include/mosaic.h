@@ -269,6 +269,8 @@ int mosaic_mfma_probe(const void *operands, float *sink, int32_t iters, int32_t 
  *                         mosaic_vmm_committed_bytes() bytes may be touched -- beyond them is unmapped
  *                         address space and an access faults.
  *   mosaic_vmm_destroy    waits for the device, unmaps, releases and frees the reservation; accepts NULL.
+ * mosaic_vmm_resize and mosaic_vmm_destroy return INVALID_ARG when the calling thread's current device is not the
+ * object's (the wait would act on the wrong device).
  * The object is owned by the caller and is not thread-safe.
  */
 typedef struct mosaic_vmm mosaic_vmm;

@@ -330,6 +330,20 @@ class VmmWorkspace:
     def granularity(self) -> int:
         return int(lib().mosaic_vmm_granularity(self._h))
 
+    def tensor(self, offset, count, dtype):
+        """A torch view of `count` elements of `dtype` at byte `offset` of the mapped prefix (no copy, no ownership:
+        it must not be used after a resize that changes the mapping)."""
+        nbytes = int(count) * torch.empty((), dtype=dtype).element_size()
+        if offset < 0 or offset + nbytes > self.committed_bytes:
+            raise ValueError("slice lies outside the mapped prefix of the range")
+
+        class _Raw:
+            pass
+        raw = _Raw()
+        raw.__cuda_array_interface__ = {"shape": (max(nbytes, 1),), "typestr": "|u1",
+                                        "data": (self.ptr + int(offset), False), "version": 2}
+        return torch.as_tensor(raw, device="cuda")[:nbytes].view(dtype)
+
     def close(self):
         h, self._h = getattr(self, "_h", None), None
         if h:

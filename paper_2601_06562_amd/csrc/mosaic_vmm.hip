@@ -83,6 +83,9 @@ int mosaic_vmm_create(int device, int64_t reserve_bytes, mosaic_vmm** out) {
 
 int mosaic_vmm_resize(mosaic_vmm* v, int64_t bytes) {
   if (v == nullptr || bytes < 0) return MOSAIC_ERR_INVALID_ARG;
+  int current = -1;   // the synchronisation below acts on the current device: it must be the object's
+  if (hipGetDevice(&current) != hipSuccess) return MOSAIC_ERR_HIP;
+  if (current != v->device) return MOSAIC_ERR_INVALID_ARG;
   const size_t want = round_up((size_t)bytes, v->granularity);
   if (want > v->reserved) return MOSAIC_ERR_WORKSPACE_TOO_SMALL;
   if (want == v->committed) return MOSAIC_OK;
@@ -139,10 +142,12 @@ const char* mosaic_vmm_last_error(const mosaic_vmm* v, int* hip_error) {
 int mosaic_vmm_destroy(mosaic_vmm* v) {
   if (v == nullptr) return MOSAIC_OK;
   int rc = MOSAIC_OK;
-  if (v->committed > 0 && hipDeviceSynchronize() != hipSuccess) rc = MOSAIC_ERR_HIP;
+  int current = -1;
+  if (v->committed > 0 && (hipGetDevice(&current) != hipSuccess || current != v->device)) rc = MOSAIC_ERR_INVALID_ARG;
+  if (rc == MOSAIC_OK && v->committed > 0 && hipDeviceSynchronize() != hipSuccess) rc = MOSAIC_ERR_HIP;
   if (rc == MOSAIC_OK && !drop_mapping(v)) rc = MOSAIC_ERR_HIP;
   if (rc == MOSAIC_OK && v->base != nullptr && hipMemAddressFree(v->base, v->reserved) != hipSuccess) rc = MOSAIC_ERR_HIP;
-  delete v;   // on a HIP error the mappings are abandoned to the process's end rather than touched again
+  delete v;   // on an error the mappings are abandoned to the process's end rather than touched again
   return rc;
 }
 

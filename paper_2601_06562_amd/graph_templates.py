@@ -58,3 +58,33 @@ def dllm_step(b, layers=2, d=64, d_ff=256, vocab=1024, logits="materialised", vo
         raise ValueError(logits)
     b.add_op("unmask", [out, idx, tokens], [tokens], NONE)
     return dict(T=T, M=M, k_ffn=k_ffn, k_logits=k_logits, h_norm=hn, out=out)
+
+
+def mask_only_tail(b, vocab_splits, scan_scratch_bytes, partial_bytes=12, row_tile=256):
+    """The tail of a denoising step that this library runs, as a template: mask compaction, the fused LM-head
+    reduction in K_logits chunks over masked rows, the split merge, top-n unmasking.  Hidden states, LM head, mask
+    and token sequence are the step's inputs (persistent: outside the workspace).
+
+    The masked-row dimension is counted in ROW TILES (R = ceil(M / row_tile)), because the kernel's chunk size is a
+    whole number of row tiles: a chunk of ceil(R / K) tiles holds partial_bytes * vocab_splits * row_tile bytes of
+    partial results per tile -- exactly the workspace the fused call asks for.  partial_bytes is 12 for the greedy
+    reduction, 20 for temperature sampling.  Returns the ids a caller needs to find the buffers in a plan."""
+    T = b.add_dim("T")
+    R = b.add_dim("R")
+    k_logits = b.add_chunk_param("K_logits", R)
+    mask = b.add_tensor("mask", 1, T, NONE, True)
+    hidden = b.add_tensor("hidden", 2, T, NONE, True)
+    tokens = b.add_tensor("tokens", 4, T, NONE, True)
+    idx = b.add_tensor("mask_idx", 4, T, NONE, False)
+    count = b.add_tensor("mask_count", 4, NONE, NONE, False)
+    scratch = b.add_tensor("scan_scratch", max(int(scan_scratch_bytes), 1), NONE, NONE, False)
+    partials = b.add_tensor("partials", partial_bytes * vocab_splits * row_tile, R, k_logits, False)
+    out_token = b.add_tensor("out_token", 4 * row_tile, R, NONE, False)
+    out_conf = b.add_tensor("out_conf", 4 * row_tile, R, NONE, False)
+    out_lse = b.add_tensor("out_lse", 4 * row_tile, R, NONE, False)
+    b.add_op("mask_compact", [mask], [idx, count, scratch], NONE)
+    b.add_op("lm_head_reduce", [hidden, idx, count], [partials], k_logits)
+    b.add_op("merge_splits", [partials, count], [out_token, out_conf, out_lse], k_logits)
+    b.add_op("unmask", [out_token, out_conf, idx, count, mask, tokens], [tokens, mask], NONE)
+    return dict(T=T, R=R, k_logits=k_logits, idx=idx, count=count, scratch=scratch, partials=partials,
+                out_token=out_token, out_conf=out_conf, out_lse=out_lse)
