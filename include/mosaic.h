@@ -152,6 +152,15 @@ int mosaic_masked_logits_reduce(const void *hidden, int64_t T, int32_t d, int64_
                                 int64_t workspace_bytes, void *stream);
 
 /*
+ * Name of the kernel (or pair of kernels) that mosaic_masked_logits_reduce (sampling = 0) or
+ * mosaic_masked_logits_sample with temperature > 0 (sampling = 1) launches for these sizes and this plan, as it
+ * appears in a profiler's kernel trace; for reports.  Host-only, static storage; "" for a NULL plan or sizes the
+ * calls reject.
+ */
+const char *mosaic_masked_logits_kernel_name(int64_t T, int32_t d, int64_t ld_h, int32_t V, const mosaic_plan *plan,
+                                             int32_t sampling);
+
+/*
  * mosaic_masked_logits_reduce for callers that cannot allocate device memory or hand in a workspace: code
  * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and
  * errors as mosaic_masked_logits_reduce, except that the partial results go to a fixed array of

@@ -29,7 +29,8 @@ STATIC_WORKSPACE_BYTES = 4 << 20   # the fixed array behind mosaic_masked_logits
 
 EXPORTS = (
     "mosaic_status_string", "mosaic_plan_workspace", "mosaic_compact_scratch_bytes", "mosaic_mask_compact",
-    "mosaic_masked_logits_reduce", "mosaic_masked_logits_reduce_static", "mosaic_sample_workspace_bytes",
+    "mosaic_masked_logits_reduce", "mosaic_masked_logits_reduce_static", "mosaic_masked_logits_kernel_name",
+    "mosaic_sample_workspace_bytes",
     "mosaic_masked_logits_sample",
     "mosaic_unmask_topn", "mosaic_shift_indices", "mosaic_mfma_probe_flops", "mosaic_mfma_probe", "mosaic_version",
     "mosaic_vmm_create", "mosaic_vmm_resize", "mosaic_vmm_ptr", "mosaic_vmm_committed_bytes",
@@ -103,6 +104,8 @@ def lib():
         L.mosaic_masked_logits_reduce_static.restype = ctypes.c_int
         L.mosaic_masked_logits_reduce_static.argtypes = [p, i64, i32, i64, p, i32, p, p, i64, p, p, p,
                                                          ctypes.POINTER(MosaicPlan), p]
+        L.mosaic_masked_logits_kernel_name.restype = ctypes.c_char_p
+        L.mosaic_masked_logits_kernel_name.argtypes = [i64, i32, i64, i32, ctypes.POINTER(MosaicPlan), i32]
         L.mosaic_sample_workspace_bytes.restype = i64
         L.mosaic_sample_workspace_bytes.argtypes = [ctypes.POINTER(MosaicPlan)]
         L.mosaic_masked_logits_sample.restype = ctypes.c_int
@@ -244,6 +247,11 @@ def mosaic_masked_logits_reduce_static(hidden, w, idx, count, max_rows, out_toke
         _dev_ptr(out_token, "out_token", torch.int32), _dev_ptr(out_conf, "out_conf", torch.float32),
         _dev_ptr(out_lse, "out_lse", torch.float32), ctypes.byref(plan), _stream_ptr(stream)),
         "mosaic_masked_logits_reduce_static")
+
+
+def mosaic_masked_logits_kernel_name(T, d, ld_h, V, plan, sampling=False) -> str:
+    """The kernel(s) the fused pass launches for these sizes and this plan (for reports)."""
+    return lib().mosaic_masked_logits_kernel_name(T, d, ld_h, V, ctypes.byref(plan), int(sampling)).decode()
 
 
 def mosaic_sample_workspace_bytes(plan) -> int:

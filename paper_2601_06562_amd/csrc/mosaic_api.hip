@@ -138,6 +138,12 @@ int mosaic_masked_logits_reduce_static(const void* hidden, int64_t T, int32_t d,
                         nullptr, 0, true, 0.f, 0, stream);
 }
 
+const char* mosaic_masked_logits_kernel_name(int64_t T, int32_t d, int64_t ld_h, int32_t V, const mosaic_plan* plan,
+                                             int32_t sampling) {
+  if (plan == nullptr || T < 0 || d <= 0 || V <= 0 || ld_h < d) return "";
+  return mosaic::masked_logits_kernel_name(T, ld_h, d, V, *plan, sampling != 0);
+}
+
 int64_t mosaic_sample_workspace_bytes(const mosaic_plan* plan) {
   if (plan == nullptr || plan->rows_per_chunk < 1 || plan->vocab_splits < 1) return 0;
   return mosaic::sample_partials_bytes(plan->rows_per_chunk, plan->vocab_splits);

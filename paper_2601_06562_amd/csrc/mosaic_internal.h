@@ -46,6 +46,9 @@ struct LogitsArgs {
   uint64_t seed = 0;
 };
 int launch_masked_logits(const LogitsArgs& a, const mosaic_plan& plan, hipStream_t stream);
+// Name(s) of the kernel(s) launch_masked_logits picks for these sizes and this plan (static storage).
+const char* masked_logits_kernel_name(int64_t T, int64_t ld_h, int32_t d, int32_t V, const mosaic_plan& plan,
+                                      bool sample);
 
 // ---- sampling tail and shifted gather (mosaic_unmask.hip)
 int launch_unmask_topn(const float* conf, const int32_t* token, const int32_t* idx, const int32_t* count,

@@ -863,6 +863,35 @@ __global__ __launch_bounds__(256) void combine_kernel(const KernelParams p) {
   p.out_conf[p.row0 + r] = sample ? __builtin_amdgcn_exp2f((xa - m) * kLog2e) / s : 1.0f / s;
 }
 
+// Which kernel(s) serve a call.  The hand-scheduled 4-wave kernel needs whole vocabulary tiles and 32-bit row
+// offsets.  A vocabulary with a ragged last tile is covered by a pair of launches: the 4-wave kernel on the whole
+// tiles with S - 1 splits and the general 8-wave kernel on the last tile as split S - 1.  Everything else (and
+// plans that ask for it) goes to the general kernel alone.
+struct KernelChoice {
+  bool fast;     // 4-wave kernel alone
+  bool paired;   // 4-wave kernel + general kernel on the ragged last vocabulary tile
+};
+static KernelChoice choose_kernel(int64_t T, int64_t ld_h, int32_t d, int32_t V, const mosaic_plan& plan) {
+  const int64_t vocab_tiles = ((int64_t)V + kTileVocab - 1) / kTileVocab;
+  const bool fast_ok = (plan.flags & MOSAIC_PLAN_GENERAL_KERNEL) == 0 &&
+                       (uint64_t)T * (uint64_t)(ld_h * 2) < ((uint64_t)1 << 32) &&
+                       (uint64_t)kTileVocab * (uint64_t)d * 2u < ((uint64_t)1 << 32);
+  KernelChoice c;
+  c.fast = fast_ok && V % kTileVocab == 0;
+  c.paired = fast_ok && !c.fast && vocab_tiles >= 2 && plan.vocab_splits >= 2;
+  return c;
+}
+
+const char* masked_logits_kernel_name(int64_t T, int64_t ld_h, int32_t d, int32_t V, const mosaic_plan& plan,
+                                      bool sample) {
+  const KernelChoice c = choose_kernel(T, ld_h, d, V, plan);
+  if (c.fast) return sample ? "masked_logits_kernel_w4<true>" : "masked_logits_kernel_w4<false>";
+  if (c.paired)
+    return sample ? "masked_logits_kernel_w4<true> + masked_logits_kernel<3,2,true> (ragged last vocabulary tile)"
+                  : "masked_logits_kernel_w4<false> + masked_logits_kernel<3,2,false> (ragged last vocabulary tile)";
+  return sample ? "masked_logits_kernel<3,2,true>" : "masked_logits_kernel<3,2,false>";
+}
+
 int launch_masked_logits(const LogitsArgs& a, const mosaic_plan& plan, hipStream_t stream) {
   KernelParams p;
   p.hidden = static_cast<const char*>(a.hidden);
@@ -895,15 +924,8 @@ int launch_masked_logits(const LogitsArgs& a, const mosaic_plan& plan, hipStream
   p.part_ym = reinterpret_cast<float*>(p.part_i + (int64_t)plan.vocab_splits * plan.rows_per_chunk);
   p.part_xa = p.part_ym + (int64_t)plan.vocab_splits * plan.rows_per_chunk;
 
-  // The hand-scheduled 4-wave kernel needs whole vocabulary tiles and 32-bit row offsets.  A vocabulary with a
-  // ragged last tile is covered by a pair of launches: the 4-wave kernel on the whole tiles with S - 1 splits and
-  // the general 8-wave kernel on the last tile as split S - 1.  Everything else (and plans that ask for it) goes
-  // to the general kernel alone.
-  const bool fast_ok = (plan.flags & MOSAIC_PLAN_GENERAL_KERNEL) == 0 &&
-                       (uint64_t)a.T * (uint64_t)p.ldh_bytes < ((uint64_t)1 << 32) &&
-                       (uint64_t)kTileVocab * (uint64_t)a.d * 2u < ((uint64_t)1 << 32);
-  const bool fast = fast_ok && a.V % kTileVocab == 0;
-  const bool paired = fast_ok && !fast && p.vocab_tiles >= 2 && plan.vocab_splits >= 2;
+  const KernelChoice choice = choose_kernel(a.T, a.ld_h, a.d, a.V, plan);
+  const bool fast = choice.fast, paired = choice.paired;
   // The selector gives a ragged vocabulary one split more than fills the chip (for the pair's second launch);
   // the general kernel alone works best without it.
   if (!fast && !paired && a.V % kTileVocab != 0 && p.vocab_tiles >= 2 && p.splits >= 2) p.splits -= 1;
