@@ -60,38 +60,64 @@ def dma_h(i):
     return [f"s_add_u32 m0, %[hdst], {98304 + 1024 * i}", "s_nop 0", f"global_load_lds_dwordx4 %[hoff{i}], {HSRC}"]
 
 
-def advance_h():
+def dma_split(i, hidden):
+    """the same copy as (m0 setup, the load): in the steady state the setup sits one MFMA ahead of the load, which
+    supplies the wait state an M0 write needs before a direct-to-LDS load"""
+    seq = dma_h(i) if hidden else dma_w(i)
+    return seq[0], seq[2]
+
+
+def advance_h_ops():
     """next hidden copy: k index, source pointer (forward 128 bytes, back nk*128 after the last K-tile), slot"""
-    e("s_add_u32 %[hk], %[hk], 1")
-    e("s_add_u32 s98, s98, 128")
-    e("s_addc_u32 s99, s99, 0")
-    e("s_cmp_eq_u32 %[hk], %[nk]")
-    e(f"s_cselect_b32 vcc_lo, {NK128}, 0")
-    e("s_cselect_b32 %[hk], 0, %[hk]")
-    e("s_sub_u32 s98, s98, vcc_lo")
-    e("s_subb_u32 s99, s99, 0")
-    e("s_xor_b32 %[hdst], %[hdst], 0x8000")
+    return ["s_add_u32 %[hk], %[hk], 1",
+            "s_add_u32 s98, s98, 128",
+            "s_addc_u32 s99, s99, 0",
+            "s_cmp_eq_u32 %[hk], %[nk]",
+            f"s_cselect_b32 vcc_lo, {NK128}, 0",
+            "s_cselect_b32 %[hk], 0, %[hk]",
+            "s_sub_u32 s98, s98, vcc_lo",
+            "s_subb_u32 s99, s99, 0",
+            "s_xor_b32 %[hdst], %[hdst], 0x8000"]
+
+
+def advance_w_ops():
+    """next LM-head copy: k index, source pointer (forward 128 bytes or on to the next 256 rows), slot"""
+    return ["s_add_u32 %[wk], %[wk], 1",
+            "s_cmp_eq_u32 %[wk], %[nk]",
+            "s_cselect_b32 vcc_lo, %[wwrap], 128",
+            "s_cselect_b32 %[wk], 0, %[wk]",
+            "s_add_u32 s96, s96, vcc_lo",
+            "s_addc_u32 s97, s97, 0",
+            "s_add_u32 %[wdst], %[wdst], 0x8000",
+            "s_cmp_ge_u32 %[wdst], 0x18000",
+            "s_cselect_b32 vcc_lo, 0x18000, 0",
+            "s_sub_u32 %[wdst], %[wdst], vcc_lo"]
+
+
+def rotate_read_slots_ops():
+    return ["s_add_u32 %[wrd], %[wrd], 0x8000",
+            "s_cmp_ge_u32 %[wrd], 0x18000",
+            "s_cselect_b32 %[wrd], 0, %[wrd]",
+            "s_xor_b32 %[hrd], %[hrd], 0x8000"]
+
+
+def read_addr_ops(ks):
+    return [f"v_add_u32 {VT0}, %[wrd], %[rdw{ks}]", f"v_add_u32 {VT1}, %[hrd], %[rdh{ks}]"]
+
+
+def advance_h():
+    for x in advance_h_ops():
+        e(x)
 
 
 def advance_w():
-    """next LM-head copy: k index, source pointer (forward 128 bytes or on to the next 256 rows), slot"""
-    e("s_add_u32 %[wk], %[wk], 1")
-    e("s_cmp_eq_u32 %[wk], %[nk]")
-    e("s_cselect_b32 vcc_lo, %[wwrap], 128")
-    e("s_cselect_b32 %[wk], 0, %[wk]")
-    e("s_add_u32 s96, s96, vcc_lo")
-    e("s_addc_u32 s97, s97, 0")
-    e("s_add_u32 %[wdst], %[wdst], 0x8000")
-    e("s_cmp_ge_u32 %[wdst], 0x18000")
-    e("s_cselect_b32 vcc_lo, 0x18000, 0")
-    e("s_sub_u32 %[wdst], %[wdst], vcc_lo")
+    for x in advance_w_ops():
+        e(x)
 
 
 def rotate_read_slots():
-    e("s_add_u32 %[wrd], %[wrd], 0x8000")
-    e("s_cmp_ge_u32 %[wrd], 0x18000")
-    e("s_cselect_b32 %[wrd], 0, %[wrd]")
-    e("s_xor_b32 %[hrd], %[hrd], 0x8000")
+    for x in rotate_read_slots_ops():
+        e(x)
 
 
 def cond_g_ge1_and(plus):
@@ -114,12 +140,33 @@ def cond_plus(plus):
 # possible time to land before the sync that publishes it, and four MFMAs apart, so the 16 KiB a workgroup
 # requests per position never queue up behind the texture addresser (denser or later placement measured slower).
 COPY_POS = [1, 5, 9, 13, 17, 21, 25, 29]
+STEADY_UNROLL = 1
+
+
+def spread(fill, first, ops, per_gap=2):
+    """book-keeping instructions `ops`, `per_gap` at a time, into the gaps after MFMA first, first + 1, ..."""
+    k = first
+    for i in range(0, len(ops), per_gap):
+        fill.setdefault(k, []).extend(ops[i:i + per_gap])
+        k += 1
+    return k
+
+
+def scheduled_group(buf, fill):
+    """64 MFMAs on fragment buffer `buf`; fill[k] = the instructions that follow MFMA k.  A wave is alone on its
+    SIMD and issues one instruction every few cycles, so whatever sits between two MFMAs beyond ~3 instructions
+    delays the second one: the steady state keeps every gap that short."""
+    order = [(bi, bj) for bi in range(8) for bj in range(8)]
+    for k in range(64):
+        mfma(*order[k], buf)
+        for x in fill.get(k, []):
+            e(x)
 
 
 def group(buf, rd=None, dma=None, cond=None, after=None, pos=None):
-    """64 MFMAs on fragment buffer `buf`.  rd = 16 ds_reads, one after each even MFMA 0..30.
-    dma = 8 copy sequences, copy i after MFMA pos[i]; guarded by `cond` when given (then the guarded span is
-    pos[0]..pos[7]); `after` runs once the copies are out."""
+    """64 MFMAs on fragment buffer `buf` for the guarded (first / last steps) path.  rd = 16 ds_reads, one after
+    each even MFMA 0..30.  dma = 8 copy sequences, copy i after MFMA pos[i]; guarded by `cond` when given (then
+    the guarded span is pos[0]..pos[7]); `after` runs once the copies are out."""
     e("s_waitcnt lgkmcnt(0)")
     order = [(bi, bj) for bi in range(8) for bj in range(8)]
     if not dma:
@@ -160,6 +207,32 @@ def group(buf, rd=None, dma=None, cond=None, after=None, pos=None):
             e(rd[k // 2])
 
 
+def steady_fill(buf):
+    """Gap contents of one steady-state group: the 16 fragment reads of the other buffer after the even MFMAs of
+    the first half, the 8 copies after every fourth MFMA of that half, and the scalar book-keeping spread over the
+    second half two instructions at a time."""
+    fill = {}
+    rd = reads(1 - buf)
+    for k in range(0, 32, 2):
+        fill.setdefault(k, []).append(rd[k // 2])
+    for i, k in enumerate(COPY_POS):
+        setup, load = dma_split(i, hidden=(buf == 1))
+        fill.setdefault(k - 1, []).append(setup)
+        fill.setdefault(k, []).append(load)
+    if buf == 0:
+        k = spread(fill, 33, advance_w_ops())
+        k = spread(fill, k + 1, rotate_read_slots_ops())     # the read slots of the NEXT tile, ahead of the sync
+        spread(fill, k + 1, read_addr_ops(0))                # addresses of its first-half fragments
+    else:
+        k = spread(fill, 33, advance_h_ops())
+        k = spread(fill, k + 1, ["s_add_u32 %[g], %[g], 1", f"s_add_u32 {KT}, {KT}, 1"])
+        spread(fill, k + 1, read_addr_ops(1))                # next step's second-half fragment addresses
+        # scc = (k-tile index < nk) && (g + 2 < total): the next step belongs to this statement and is steady
+        spread(fill, 60, ["s_add_u32 vcc_lo, %[g], 2", "s_cmp_lt_u32 vcc_lo, %[total]",
+                          "s_cselect_b32 vcc_lo, %[nk], 0", f"s_cmp_lt_u32 {KT}, vcc_lo"])
+    return fill
+
+
 def step_end(top):
     e("s_add_u32 %[g], %[g], 1")
     e(f"s_add_u32 {KT}, {KT}, 1")
@@ -179,21 +252,28 @@ def build():
     for r in reads(0):
         e(r)
     e("s_nop 7")
-    top, generic, out = label("top"), label("generic"), label("out")
+    top, steady, generic, out = label("top"), label("steady"), label("generic"), label("out")
     e(f"{top}:")
-    # Steady state (1 <= g and g + 2 < total): every copy and the sync happen, no branch inside the body.
+    # Steady state (1 <= g and g + 2 < total): every copy and the sync happen, no branch inside the body, one taken
+    # branch per step (the back edge, issued right behind the last MFMA).
     cond_g_ge1_and(2)
     e(f"s_cbranch_scc0 {generic}")
     read_addr(1)
-    group(0, rd=reads(1), dma=[dma_w(i) for i in range(8)], after=advance_w, pos=COPY_POS)     # LM-head tile g+2
-    e("s_waitcnt lgkmcnt(0)")
-    e("s_waitcnt vmcnt(8)")       # all but the LM-head tile just issued
-    e("s_barrier")
-    rotate_read_slots()
-    read_addr(0)
-    group(1, rd=reads(0), dma=[dma_h(i) for i in range(8)], after=advance_h, pos=COPY_POS)     # hidden tile g+2
-    step_end(top)
-    e(f"s_branch {out}")
+    e(f"{steady}:")
+    leave = label("leave")
+    for copy in range(STEADY_UNROLL):                        # a taken branch costs more than an MFMA: one per
+        e("s_waitcnt lgkmcnt(0)")                            # STEADY_UNROLL steps
+        scheduled_group(0, steady_fill(0))                   # LM-head tile g+2 goes out
+        e("s_waitcnt vmcnt(8) lgkmcnt(0)")                   # all copies but the LM-head tile just issued; fragments
+        e("s_barrier")
+        scheduled_group(1, steady_fill(1))                   # hidden tile g+2 goes out
+        if copy + 1 < STEADY_UNROLL:
+            e(f"s_cbranch_scc0 {leave}")
+        else:
+            e(f"s_cbranch_scc1 {steady}")
+    e(f"{leave}:")
+    e(f"s_cmp_lt_u32 {KT}, %[nk]")
+    e(f"s_cbranch_scc0 {out}")
     # First step and the last two: same schedule with every part guarded.
     e(f"{generic}:")
     read_addr(1)
@@ -213,7 +293,8 @@ def build():
     e(f"{stepend}:")
     step_end(top)
     e(f"{out}:")
-    # exit: results visible to the VALU, pointers back to the operands
+    # exit: no fragment read may still be in flight, results visible to the VALU, pointers back to the operands
+    e("s_waitcnt lgkmcnt(0)")
     e("s_nop 15")
     e("s_nop 15")
     e("s_mov_b32 %[wsrc_lo], s96")
