@@ -56,6 +56,8 @@ const char *mosaic_status_string(int status);
 #define MOSAIC_VOCAB_TILE 256
 #define MOSAIC_K_TILE 64
 #define MOSAIC_MAX_VOCAB_SPLITS 256
+/* Bytes at the end of every workspace for the round counters of the persistent grid (see mosaic_plan_workspace). */
+#define MOSAIC_SYNC_BYTES 1024
 
 /* Result of the chunk-size selector.  All fields are filled by mosaic_plan_workspace;
  * callers may read them and may set `flags`, nothing else. */
@@ -85,10 +87,12 @@ typedef struct {
  * budget_bytes even with a single vocabulary split, K is raised by one; stops at the
  * first K that fits (the minimal one) and fails with MOSAIC_ERR_WORKSPACE_TOO_SMALL
  * when even one row tile with one split does not fit (the non-chunkable floor).
- * The workspace is 12 * S * C bytes (one (max, sum-exp, arg-max) triple per row and
- * vocabulary split) -- never O(C * V); 20 * S * C when the plan is for a sampling step
- * (mosaic_masked_logits_sample with temperature > 0 keeps two more values per partial), so
- * that the budget bounds what that call really needs.
+ * The workspace is 12 * S * C + MOSAIC_SYNC_BYTES bytes (one (max, sum-exp, arg-max) triple per
+ * row and vocabulary split, and a fixed kilobyte of counters on which the workgroups of a launch
+ * that each take several units meet between units) -- never O(C * V); 20 * S * C +
+ * MOSAIC_SYNC_BYTES when the plan is for a sampling step (mosaic_masked_logits_sample with
+ * temperature > 0 keeps two more values per partial), so that the budget bounds what that call
+ * really needs.
  *   T          total positions, >= 0, < 2^31
  *   max_rows   host-side upper bound on M (the search in the paper is driven by the
  *              number of masks and the number of tokens; pass T if M is unknown), 0..T
@@ -166,7 +170,7 @@ const char *mosaic_masked_logits_kernel_name(int64_t T, int32_t d, int64_t ld_h,
  * errors as mosaic_masked_logits_reduce, except that the partial results go to a fixed array of
  * MOSAIC_STATIC_WORKSPACE_BYTES inside the library's device image instead of a caller's `workspace`; the call
  * itself allocates and frees nothing.
- *   plan   must need at most MOSAIC_STATIC_WORKSPACE_BYTES (12 * rows_per_chunk * vocab_splits bytes), else
+ *   plan   must need at most MOSAIC_STATIC_WORKSPACE_BYTES (plan->workspace_bytes of a greedy plan), else
  *          MOSAIC_ERR_WORKSPACE_TOO_SMALL and nothing is enqueued: make the plan with
  *          budget_bytes = MOSAIC_STATIC_WORKSPACE_BYTES and the selector chunks the rows to fit
  * Every GPU the library runs on holds one copy of the array until the process ends, and every call on a GPU uses
@@ -201,8 +205,8 @@ int mosaic_masked_logits_reduce_static(const void *hidden, int64_t T, int32_t d,
  *              p - 1, and a sequence start s and s + 1 both read row s); passing the unshifted positions
  *              here keeps the draws of different positions independent.  Any int32 value is valid
  *   workspace  dev, >= mosaic_sample_workspace_bytes(plan) when temperature > 0 (20 bytes per row of a
- *              chunk and vocabulary split instead of 12; plan->workspace_bytes already says so when the
- *              plan was made with sampling = 1), 16-byte aligned
+ *              chunk and vocabulary split instead of 12, plus MOSAIC_SYNC_BYTES; plan->workspace_bytes
+ *              already says so when the plan was made with sampling = 1), 16-byte aligned
  *   seed       any value; callers advance it per denoising step
  * Additional errors: INVALID_ARG for a negative, NaN or infinite temperature.
  * mosaic_sample_workspace_bytes returns 0 for a NULL or unfilled plan.

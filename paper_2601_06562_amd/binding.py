@@ -26,6 +26,7 @@ K_TILE = 64
 PLAN_GENERAL_KERNEL = 1   # plan.flags bit: force the general 8-wave kernel
 PLAN_SAMPLING = 2         # plan.flags bit: sized for a sampling step (20 bytes per partial)
 STATIC_WORKSPACE_BYTES = 4 << 20   # the fixed array behind mosaic_masked_logits_reduce_static
+SYNC_BYTES = 1024                  # round counters at the end of every workspace
 
 EXPORTS = (
     "mosaic_status_string", "mosaic_plan_workspace", "mosaic_compact_scratch_bytes", "mosaic_mask_compact",

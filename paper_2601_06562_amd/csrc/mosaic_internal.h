@@ -46,6 +46,12 @@ struct LogitsArgs {
   uint64_t seed = 0;
 };
 int launch_masked_logits(const LogitsArgs& a, const mosaic_plan& plan, hipStream_t stream);
+// Which kernel(s) serve a call (host-side decision, mosaic_plan.cpp).
+struct KernelChoice {
+  bool fast;     // 4-wave kernel alone
+  bool paired;   // 4-wave kernel + general kernel on the ragged last vocabulary tile
+};
+KernelChoice choose_kernel(int64_t T, int64_t ld_h, int32_t d, int32_t V, const mosaic_plan& plan);
 // Name(s) of the kernel(s) launch_masked_logits picks for these sizes and this plan (static storage).
 const char* masked_logits_kernel_name(int64_t T, int64_t ld_h, int32_t d, int32_t V, const mosaic_plan& plan,
                                       bool sample);

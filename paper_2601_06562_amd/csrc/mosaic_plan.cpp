@@ -5,17 +5,22 @@
 // the operator that forms the peak by one, re-evaluates the footprint, and stops at the first
 // configuration that fits, or fails when only non-chunkable memory is left.  On this path the one
 // chunkable buffer is the array of partial (max, sum-exp, arg-max) triples, 12 bytes per row and
-// vocabulary split (20 when the step samples with a temperature: two more values per partial); its
-// non-chunkable floor is one row tile with one split.
+// vocabulary split (20 when the step samples with a temperature: two more values per partial), plus a fixed
+// MOSAIC_SYNC_BYTES of round counters; its non-chunkable floor is one row tile with one split.
 #include <stdint.h>
 
 #include "mosaic_internal.h"
 
 namespace mosaic {
 
-int64_t partials_bytes(int64_t rows_padded, int32_t splits) { return 12 * rows_padded * (int64_t)splits; }
+// Workspace of one chunk: the partial results plus the round counters of the persistent grid.
+int64_t partials_bytes(int64_t rows_padded, int32_t splits) {
+  return 12 * rows_padded * (int64_t)splits + MOSAIC_SYNC_BYTES;
+}
 // sampling keeps two more planes per row and split (best perturbed score, the plain logit there)
-int64_t sample_partials_bytes(int64_t rows_padded, int32_t splits) { return 20 * rows_padded * (int64_t)splits; }
+int64_t sample_partials_bytes(int64_t rows_padded, int32_t splits) {
+  return 20 * rows_padded * (int64_t)splits + MOSAIC_SYNC_BYTES;
+}
 
 // Number of vocabulary splits for `row_tiles` row tiles: the workgroups walk their units in rounds of
 // `num_cus`; a round lasts as long as its longest unit.  Pick the S that minimises
@@ -40,6 +45,31 @@ int32_t choose_vocab_splits(int64_t row_tiles, int64_t vocab_tiles, int32_t num_
     }
   }
   return best;
+}
+
+// Which kernel(s) serve a call.  The hand-scheduled 4-wave kernel needs whole vocabulary tiles and 32-bit row
+// offsets.  A vocabulary with a ragged last tile is covered by a pair of launches: the 4-wave kernel on the whole
+// tiles with S - 1 splits and the general 8-wave kernel on the last tile as split S - 1.  Everything else (and
+// plans that ask for it) goes to the general kernel alone.
+KernelChoice choose_kernel(int64_t T, int64_t ld_h, int32_t d, int32_t V, const mosaic_plan& plan) {
+  const int64_t vocab_tiles = ((int64_t)V + MOSAIC_VOCAB_TILE - 1) / MOSAIC_VOCAB_TILE;
+  const bool fast_ok = (plan.flags & MOSAIC_PLAN_GENERAL_KERNEL) == 0 &&
+                       (uint64_t)T * (uint64_t)(ld_h * 2) < ((uint64_t)1 << 32) &&
+                       (uint64_t)MOSAIC_VOCAB_TILE * (uint64_t)d * 2u < ((uint64_t)1 << 32);
+  KernelChoice c;
+  c.fast = fast_ok && V % MOSAIC_VOCAB_TILE == 0;
+  c.paired = fast_ok && !c.fast && vocab_tiles >= 2 && plan.vocab_splits >= 2;
+  return c;
+}
+
+const char* masked_logits_kernel_name(int64_t T, int64_t ld_h, int32_t d, int32_t V, const mosaic_plan& plan,
+                                      bool sample) {
+  const KernelChoice c = choose_kernel(T, ld_h, d, V, plan);
+  if (c.fast) return sample ? "masked_logits_kernel_w4<true>" : "masked_logits_kernel_w4<false>";
+  if (c.paired)
+    return sample ? "masked_logits_kernel_w4<true> + masked_logits_kernel<3,2,true> (ragged last vocabulary tile)"
+                  : "masked_logits_kernel_w4<false> + masked_logits_kernel<3,2,false> (ragged last vocabulary tile)";
+  return sample ? "masked_logits_kernel<3,2,true>" : "masked_logits_kernel<3,2,false>";
 }
 
 }  // namespace mosaic
@@ -67,7 +97,8 @@ extern "C" int mosaic_plan_workspace(int64_t T, int64_t max_rows, int32_t d, int
     if (S > MOSAIC_MAX_VOCAB_SPLITS) S = MOSAIC_MAX_VOCAB_SPLITS;
     if (budget_bytes > 0) {
       // splits the budget allows (a sampling step keeps 20 bytes per row and split, a greedy one 12)
-      const int64_t fit = budget_bytes / (sampling ? sample_partials_bytes(C, 1) : partials_bytes(C, 1));
+      const int64_t per_split = (sampling ? 20 : 12) * C;
+      const int64_t fit = budget_bytes > MOSAIC_SYNC_BYTES ? (budget_bytes - MOSAIC_SYNC_BYTES) / per_split : 0;
       if (fit < S) S = fit;
     }
     if (S >= 1) {

@@ -60,15 +60,16 @@ def dllm_step(b, layers=2, d=64, d_ff=256, vocab=1024, logits="materialised", vo
     return dict(T=T, M=M, k_ffn=k_ffn, k_logits=k_logits, h_norm=hn, out=out)
 
 
-def mask_only_tail(b, vocab_splits, scan_scratch_bytes, partial_bytes=12, row_tile=256):
+def mask_only_tail(b, vocab_splits, scan_scratch_bytes, partial_bytes=12, row_tile=256, sync_bytes=1024):
     """The tail of a denoising step that this library runs, as a template: mask compaction, the fused LM-head
     reduction in K_logits chunks over masked rows, the split merge, top-n unmasking.  Hidden states, LM head, mask
     and token sequence are the step's inputs (persistent: outside the workspace).
 
     The masked-row dimension is counted in ROW TILES (R = ceil(M / row_tile)), because the kernel's chunk size is a
     whole number of row tiles: a chunk of ceil(R / K) tiles holds partial_bytes * vocab_splits * row_tile bytes of
-    partial results per tile -- exactly the workspace the fused call asks for.  partial_bytes is 12 for the greedy
-    reduction, 20 for temperature sampling.  Returns the ids a caller needs to find the buffers in a plan."""
+    partial results per tile; the fixed sync_bytes of round counters that close the fused call's workspace are
+    counted once per tile, so that a chunk's block is never smaller than what the call asks for.  partial_bytes is
+    12 for the greedy reduction, 20 for temperature sampling.  Returns the ids a caller needs to find the buffers in a plan."""
     T = b.add_dim("T")
     R = b.add_dim("R")
     k_logits = b.add_chunk_param("K_logits", R)
@@ -78,7 +79,7 @@ def mask_only_tail(b, vocab_splits, scan_scratch_bytes, partial_bytes=12, row_ti
     idx = b.add_tensor("mask_idx", 4, T, NONE, False)
     count = b.add_tensor("mask_count", 4, NONE, NONE, False)
     scratch = b.add_tensor("scan_scratch", max(int(scan_scratch_bytes), 1), NONE, NONE, False)
-    partials = b.add_tensor("partials", partial_bytes * vocab_splits * row_tile, R, k_logits, False)
+    partials = b.add_tensor("partials", partial_bytes * vocab_splits * row_tile + sync_bytes, R, k_logits, False)
     out_token = b.add_tensor("out_token", 4 * row_tile, R, NONE, False)
     out_conf = b.add_tensor("out_conf", 4 * row_tile, R, NONE, False)
     out_lse = b.add_tensor("out_lse", 4 * row_tile, R, NONE, False)

@@ -20,7 +20,7 @@ def run_hip(hidden, w, mask, max_rows=None, budget_bytes=0, plan_edit=None, sync
     op = binding.MaskOnlyLogits(T, d, V, max_rows=max_rows, budget_bytes=budget_bytes, device=hidden.device)
     if plan_edit is not None:
         plan_edit(op.plan)
-        need = 12 * op.plan.rows_per_chunk * op.plan.vocab_splits
+        need = 12 * op.plan.rows_per_chunk * op.plan.vocab_splits + binding.SYNC_BYTES
         op.plan.workspace_bytes = need
         op.workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=hidden.device)
     # poison outputs so that untouched entries are detectable

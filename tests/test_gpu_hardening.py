@@ -40,7 +40,7 @@ class GuardedStep:
         if plan_edit is not None:
             plan_edit(self.plan)
             per = 20 if sampling else 12
-            self.plan.workspace_bytes = per * self.plan.rows_per_chunk * self.plan.vocab_splits
+            self.plan.workspace_bytes = per * self.plan.rows_per_chunk * self.plan.vocab_splits + binding.SYNC_BYTES
         self.max_rows = max_rows
         self.idx = Guarded(max(T, 1), torch.int32, -7)
         self.count = Guarded(1, torch.int32, 0)
@@ -216,7 +216,7 @@ def test_budget_bounds_the_sampling_workspace_on_the_device():
     print("sampling budget", flush=True)
     T, d, V, tau, seed = 3000, 128, 2048, 0.9, 77
     wl = workloads.small_random(T, d, V, p=1.0, seed=4, device=DEV)
-    budget = 20 * 256 * 3 + 100                                 # one row tile x 3 splits x 20 bytes, and a bit
+    budget = 20 * 256 * 3 + binding.SYNC_BYTES + 100           # one row tile x 3 splits x 20 bytes, the counters, a bit
     free = binding.MaskOnlyLogits(T, d, V, device=DEV, sampling=True)
     tight = binding.MaskOnlyLogits(T, d, V, device=DEV, sampling=True, budget_bytes=budget)
     assert free.plan.num_chunks == 1

@@ -31,7 +31,7 @@ def test_searched_plan_on_mapped_pages_runs_the_chunked_step(name, want_chunks):
 
     # (1) template, (3) search: the smallest budget that K_logits = want_chunks meets is the planned peak at that K
     g = binding.GraphTemplate()
-    ids = graph_templates.mask_only_tail(g, S, binding.mosaic_compact_scratch_bytes(T))
+    ids = graph_templates.mask_only_tail(g, S, binding.mosaic_compact_scratch_bytes(T), sync_bytes=binding.SYNC_BYTES)
     _, at_k = g.plan([T, R], [want_chunks], placements=False)
     _, below = g.plan([T, R], [want_chunks - 1], placements=False)
     budget = at_k["peak_bytes"]
@@ -46,9 +46,10 @@ def test_searched_plan_on_mapped_pages_runs_the_chunked_step(name, want_chunks):
     tiles_per_chunk = -(-R // want_chunks)
     C = tiles_per_chunk * ROW_TILE
     part = [where[(ids["partials"], it)] for it in range(want_chunks)]
-    assert all(p["bytes"] == 12 * S * C for p in part)
+    need = 12 * S * C + binding.SYNC_BYTES                  # what the fused call asks for
+    assert all(need <= p["bytes"] <= need + tiles_per_chunk * binding.SYNC_BYTES for p in part)
     assert len({p["offset"] for p in part}) == 1            # consecutive chunks reuse one slot of the workspace
-    naive = 12 * S * R * ROW_TILE
+    naive = 12 * S * R * ROW_TILE + R * binding.SYNC_BYTES
     assert summary["peak_bytes"] <= budget < naive + 4 * T
 
     # (2) reserve once, (5) bind pages up to the planned peak
@@ -78,7 +79,7 @@ def test_searched_plan_on_mapped_pages_runs_the_chunked_step(name, want_chunks):
     plan = binding.MosaicPlan.from_buffer_copy(unbounded)
     plan.num_chunks = -(-M // C)
     plan.rows_per_chunk = C
-    plan.workspace_bytes = 12 * S * C
+    plan.workspace_bytes = need
     plan.grid = min(256, tiles_per_chunk * S)
     assert plan.num_chunks == want_chunks
     binding.mosaic_mask_compact(wl.mask, idx, count, scratch)

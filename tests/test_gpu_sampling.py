@@ -27,7 +27,7 @@ def run_sample(wl, tau, seed, budget_bytes=0, plan_edit=None, max_rows=None):
                                 sampling=True)
     if plan_edit is not None:
         plan_edit(op.plan)
-        op.plan.workspace_bytes = 12 * op.plan.rows_per_chunk * op.plan.vocab_splits
+        op.plan.workspace_bytes = 12 * op.plan.rows_per_chunk * op.plan.vocab_splits + binding.SYNC_BYTES
         op.workspace = torch.empty(max(binding.mosaic_sample_workspace_bytes(op.plan), 16), dtype=torch.uint8,
                                    device=DEV)
     op.token.fill_(-7)
@@ -126,7 +126,7 @@ def test_sample_is_a_function_of_seed_position_and_id_only():
     M = base["M"]
     again = run_sample(wl, 1.0, 42)
     assert np.array_equal(base["tok"][:M], again["tok"][:M])
-    chunked = run_sample(wl, 1.0, 42, budget_bytes=12 * 512 * 1)
+    chunked = run_sample(wl, 1.0, 42, budget_bytes=12 * 512 * 1 + binding.SYNC_BYTES)
     assert chunked["op"].plan.num_chunks > 1
     assert np.array_equal(base["tok"][:M], chunked["tok"][:M])
     assert np.abs(base["lse"][:M] - chunked["lse"][:M]).max() <= 1e-5

@@ -30,7 +30,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def workspace(C, S, per_partial=12):
-    return per_partial * C * S
+    return per_partial * C * S + binding.SYNC_BYTES
 
 
 def brute_force_min_chunks(max_rows, budget, per_partial=12):
@@ -52,7 +52,7 @@ def test_selector_unbounded_is_one_chunk(rows):
 
 
 @pytest.mark.parametrize("rows", [300, 4096, 5000, 58491])
-@pytest.mark.parametrize("budget", [3072, 3073, 12 * 256 * 7, 12 * 1024, 12 * 4096, 100000, 10 ** 6])
+@pytest.mark.parametrize("budget", [4096, 4097, 12 * 256 * 7, 12 * 1024 + 1024, 12 * 4096 + 1024, 100000, 10 ** 6])
 def test_selector_matches_brute_force(rows, budget):
     plan = binding.mosaic_plan_workspace(131072, rows, 4096, 126464, budget)
     K, C = brute_force_min_chunks(rows, budget)
@@ -66,7 +66,7 @@ def test_selector_matches_brute_force(rows, budget):
 
 
 @pytest.mark.parametrize("rows", [300, 4096, 5000, 58491])
-@pytest.mark.parametrize("budget", [5120, 5121, 20 * 256 * 7, 12 * 4096, 20 * 4096, 100000, 10 ** 6])
+@pytest.mark.parametrize("budget", [6144, 6145, 20 * 256 * 7, 12 * 4096 + 1024, 20 * 4096 + 1024, 100000, 10 ** 6])
 def test_selector_bounds_the_sampling_workspace(rows, budget):
     """A plan for a sampling step keeps 20 bytes per row and split; the budget bounds THAT (section 4.4: the search
     stops only at a configuration that fits), with the same minimal-K rule."""
@@ -74,29 +74,29 @@ def test_selector_bounds_the_sampling_workspace(rows, budget):
     assert plan.flags & binding.PLAN_SAMPLING
     K, C = brute_force_min_chunks(rows, budget, per_partial=20)
     assert plan.rows_per_chunk == C and plan.num_chunks == -(-rows // C)
-    assert plan.workspace_bytes == 20 * plan.rows_per_chunk * plan.vocab_splits <= budget
+    assert plan.workspace_bytes == workspace(plan.rows_per_chunk, plan.vocab_splits, 20) <= budget
     assert binding.mosaic_sample_workspace_bytes(plan) == plan.workspace_bytes
     greedy = binding.mosaic_plan_workspace(131072, rows, 4096, 126464, budget)
     assert not greedy.flags & binding.PLAN_SAMPLING and greedy.num_chunks <= plan.num_chunks
-    assert greedy.workspace_bytes == 12 * greedy.rows_per_chunk * greedy.vocab_splits <= budget
+    assert greedy.workspace_bytes == workspace(greedy.rows_per_chunk, greedy.vocab_splits) <= budget
 
 
 def test_sampling_selector_floor_and_unbounded_size():
     with pytest.raises(binding.MosaicError) as e:
-        binding.mosaic_plan_workspace(4096, 4096, 4096, 126464, 5119, sampling=True)      # 20 * 256 - 1
+        binding.mosaic_plan_workspace(4096, 4096, 4096, 126464, 6143, sampling=True)      # 20 * 256 + 1024 - 1
     assert e.value.status == binding.MOSAIC_ERR_WORKSPACE_TOO_SMALL
-    assert binding.mosaic_plan_workspace(4096, 4096, 4096, 126464, 5120, sampling=True).rows_per_chunk == 256
+    assert binding.mosaic_plan_workspace(4096, 4096, 4096, 126464, 6144, sampling=True).rows_per_chunk == 256
     a = binding.mosaic_plan_workspace(4096, 4096, 4096, 126464, 0)
     b = binding.mosaic_plan_workspace(4096, 4096, 4096, 126464, 0, sampling=True)
     assert (a.num_chunks, a.rows_per_chunk, a.vocab_splits, a.grid) == (b.num_chunks, b.rows_per_chunk, b.vocab_splits, b.grid)
-    assert b.workspace_bytes * 12 == a.workspace_bytes * 20
+    assert (b.workspace_bytes - binding.SYNC_BYTES) * 12 == (a.workspace_bytes - binding.SYNC_BYTES) * 20
 
 
 def test_selector_failure_is_exactly_the_non_chunkable_floor():
     with pytest.raises(binding.MosaicError) as e:
-        binding.mosaic_plan_workspace(4096, 4096, 4096, 126464, 3071)
+        binding.mosaic_plan_workspace(4096, 4096, 4096, 126464, 4095)
     assert e.value.status == binding.MOSAIC_ERR_WORKSPACE_TOO_SMALL
-    assert binding.mosaic_plan_workspace(4096, 4096, 4096, 126464, 3072).rows_per_chunk == 256
+    assert binding.mosaic_plan_workspace(4096, 4096, 4096, 126464, 4096).rows_per_chunk == 256
 
 
 def test_selector_split_choice_fills_the_chip():
@@ -175,6 +175,7 @@ def test_static_workspace_entry_point_validates_before_touching_the_device():
     assert fits.workspace_bytes <= binding.STATIC_WORKSPACE_BYTES
     header = open(os.path.join(ROOT, "include", "mosaic.h")).read()
     assert "#define MOSAIC_STATIC_WORKSPACE_BYTES (4 << 20)" in header and binding.STATIC_WORKSPACE_BYTES == 4 << 20
+    assert "#define MOSAIC_SYNC_BYTES 1024" in header and binding.SYNC_BYTES == 1024
 
 
 def test_sampling_tail_entry_points_validate_before_launch():
@@ -205,7 +206,7 @@ def test_sampling_entry_point_validates_before_launch():
     null, fake = ctypes.c_void_p(0), ctypes.c_void_p(0x1000)
     plan = binding.mosaic_plan_workspace(4096, 4096, 4096, 126464, 0)
     need = binding.mosaic_sample_workspace_bytes(plan)
-    assert need == 20 * plan.rows_per_chunk * plan.vocab_splits            # five fp32/int32 planes per row and split
+    assert need == 20 * plan.rows_per_chunk * plan.vocab_splits + binding.SYNC_BYTES   # five planes per row and split
     assert need > plan.workspace_bytes
     assert L.mosaic_sample_workspace_bytes(None) == 0
     call = lambda **kw: L.mosaic_masked_logits_sample(
@@ -257,5 +258,5 @@ def test_selector_keeps_at_least_four_splits_for_cache_sharing():
     for rows in (65536, 131072, 16384 * 3):
         assert binding.mosaic_plan_workspace(rows, rows, 4096, 126464, 0).vocab_splits >= 4
     assert binding.mosaic_plan_workspace(65536, 65536, 4096, 512, 0).vocab_splits == 2        # only two tiles
-    tight = binding.mosaic_plan_workspace(65536, 65536, 4096, 126464, 12 * 65536)            # budget for one split
+    tight = binding.mosaic_plan_workspace(65536, 65536, 4096, 126464, 12 * 65536 + 1024)     # budget for one split
     assert tight.vocab_splits == 1 and tight.num_chunks == 1
