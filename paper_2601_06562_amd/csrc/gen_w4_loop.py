@@ -32,8 +32,24 @@ def label(name):
     return f"L{name}{uid[0]}_%="
 
 
+# Accumulators: operands of the statement ("+a", for the kernel whose epilogue is C++), or, when the statement
+# reduces the tile itself, the AGPR file by number: block (bi, bj) = a[(bi*8 + bj)*4 .. +3].
+LITERAL_ACC = [False]
+
+
+def acc_block(bi, bj):
+    if LITERAL_ACC[0]:
+        base = (bi * 8 + bj) * 4
+        return f"a[{base}:{base + 3}]"
+    return f"%[a{bi}{bj}]"
+
+
+def acc_reg(bi, bj, r):
+    return f"a{(bi * 8 + bj) * 4 + r}"
+
+
 def mfma(bi, bj, buf):
-    e(f"v_mfma_f32_16x16x32_bf16 %[a{bi}{bj}], {FA[buf][bi]}, {FB[buf][bj]}, %[a{bi}{bj}]")
+    e(f"v_mfma_f32_16x16x32_bf16 {acc_block(bi, bj)}, {FA[buf][bi]}, {FB[buf][bj]}, {acc_block(bi, bj)}")
 
 
 def read_addr(ks):
@@ -240,6 +256,78 @@ def step_end(top):
     e(f"s_cbranch_scc1 {top}")
 
 
+LOG2E = 0x3FB8AA3B        # fp32 1.4426950408889634
+NEG_LOG2E = 0xBFB8AA3B
+X = [f"%[x{i}]" for i in range(32)]
+ET, EMN, ENML, ESEL, EY = "%[et]", "%[emn]", "%[enml]", "%[esel]", "%[ey]"
+MASK = ["s[88:89]", "s[90:91]", "s[92:93]"]
+
+
+def reduce_column(tb):
+    """The vocabulary reduction of one token column of the finished tile (this lane: 8 blocks x 4 ids, element
+    e = 4*bi + r is vocabulary id vb + 16*bi + r) into the running (max, sum-exp, arg-max) of the column:
+        t = max_e x[e];  sel = lowest e with x[e] == t;  if t > m: i = vb + code(sel)
+        mn = max(m, t);  s = s * 2^((m - mn) log2 e) + sum_e 2^(x[e] log2 e - mn log2 e);  m = mn
+    Written so that no instruction needs a wait state: a comparison result is consumed three instructions later
+    (three SGPR pairs in rotation), an exponential at the earliest two instructions later."""
+    M, S, I = f"%[m{tb}]", f"%[s{tb}]", f"%[i{tb}]"
+    for el in range(32):
+        e(f"v_accvgpr_read_b32 {X[el]}, {acc_reg(el // 4, tb, el % 4)}")
+    e(f"v_max3_f32 {ET}, {X[0]}, {X[1]}, {X[2]}")
+    for j in range(14):
+        e(f"v_max3_f32 {ET}, {ET}, {X[3 + 2 * j]}, {X[4 + 2 * j]}")
+    e(f"v_max_f32 {ET}, {ET}, {X[31]}")
+    # lowest element attaining the maximum: descending scan, a lower match overwrites a higher one
+    e(f"v_mov_b32 {ESEL}, 0")
+    order = list(range(31, -1, -1))
+    pending = []
+    for n, el in enumerate(order):
+        mask = MASK[n % 3]
+        e(f"v_cmp_eq_f32_e64 {mask}, {X[el]}, {ET}")
+        pending.append((mask, el))
+        if len(pending) == 3:
+            mk, pe = pending.pop(0)
+            e(f"v_cndmask_b32_e64 {ESEL}, {ESEL}, {pe}, {mk}")
+    # two selects are still pending; the new-maximum test and the running maximum fill the wait states
+    e(f"v_cmp_gt_f32 vcc, {ET}, {M}")                 # strict: an equal maximum in a later tile has a higher id
+    e(f"v_max_f32 {EMN}, {M}, {ET}")
+    for mk, pe in pending:
+        e(f"v_cndmask_b32_e64 {ESEL}, {ESEL}, {pe}, {mk}")
+    e(f"v_lshrrev_b32 {EY}, 2, {ESEL}")               # code = 16 * (sel / 4) + sel % 4
+    e(f"v_and_b32 {ESEL}, 3, {ESEL}")
+    e(f"v_lshl_add_u32 {ESEL}, {EY}, 4, {ESEL}")
+    e(f"v_add_u32 {ESEL}, %[vb], {ESEL}")
+    e(f"v_cndmask_b32 {I}, {I}, {ESEL}, vcc")
+    # rescale of the running sum, the common exponent offset
+    e(f"v_sub_f32 {EY}, {M}, {EMN}")
+    e(f"v_mul_f32 {EY}, {hex(LOG2E)}, {EY}")
+    e(f"v_exp_f32 {EY}, {EY}")
+    e(f"v_mul_f32 {ENML}, {hex(NEG_LOG2E)}, {EMN}")
+    e(f"v_mov_b32 {M}, {EMN}")
+    for el in range(32):
+        e(f"v_fmamk_f32 {X[el]}, {X[el]}, {hex(LOG2E)}, {ENML}")
+    for el in range(32):
+        e(f"v_exp_f32 {X[el]}, {X[el]}")
+    for step in range(1, 8):                          # four running sums, elements r, r + 4, r + 8, ...
+        for r in range(4):
+            e(f"v_add_f32 {X[r]}, {X[r]}, {X[4 * step + r]}")
+    e(f"v_add_f32 {X[0]}, {X[0]}, {X[1]}")
+    e(f"v_add_f32 {X[2]}, {X[2]}, {X[3]}")
+    e(f"v_add_f32 {X[0]}, {X[0]}, {X[2]}")
+    e(f"v_fma_f32 {S}, {S}, {EY}, {X[0]}")
+
+
+def build_tile():
+    """The statement of the greedy kernel: clear the accumulators, the K-loop, then the reduction of the tile."""
+    LITERAL_ACC[0] = True
+    for i in range(256):
+        e(f"v_accvgpr_write_b32 a{i}, 0")
+    build()
+    for tb in range(8):
+        reduce_column(tb)
+    LITERAL_ACC[0] = False
+
+
 def build():
     # entry: pointers into fixed SGPR pairs, first fragments of the current step
     e("s_mov_b32 s96, %[wsrc_lo]")
@@ -303,9 +391,20 @@ def build():
     e("s_mov_b32 %[hsrc_hi], s99")
 
 
-def main(path):
-    build()
-    outs = [f'[a{bi}{bj}] "+a"(acc[{bi}][{bj}])' for bi in range(8) for bj in range(8)]
+def write_statement(path, fused):
+    lines.clear()
+    uid[0] = 1000 if fused else 0
+    if fused:
+        build_tile()
+        outs = []
+        for tb in range(8):
+            outs += [f'[m{tb}] "+v"(run_m[{tb}])', f'[s{tb}] "+v"(run_s[{tb}])', f'[i{tb}] "+v"(run_i[{tb}])']
+        outs += [f'[x{i}] "=&v"(red_x[{i}])' for i in range(32)]
+        outs += ['[et] "=&v"(red_t)', '[emn] "=&v"(red_mn)', '[enml] "=&v"(red_nml)', '[esel] "=&v"(red_sel)',
+                 '[ey] "=&v"(red_y)']
+    else:
+        build()
+        outs = [f'[a{bi}{bj}] "+a"(acc[{bi}][{bj}])' for bi in range(8) for bj in range(8)]
     for name in ("wsrc_lo", "wsrc_hi", "hsrc_lo", "hsrc_hi", "wrd", "hrd", "wdst", "hdst", "wk", "hk", "g"):
         outs.append(f'[{name}] "+s"(st_{name})')
     for b in range(2):
@@ -326,10 +425,14 @@ def main(path):
         ins.append(f'[hoff{i}] "v"(hoff[{i}])')
     for name in ("total", "nk", "wwrap", "hwrap"):
         ins.append(f'[{name}] "s"(st_{name})')
-    clob = ['"s94"', '"s95"', '"s96"', '"s97"', '"s98"', '"s99"', '"vcc"', '"scc"', '"m0"',
-                                                     '"memory"']
+    clob = ['"s94"', '"s95"', '"s96"', '"s97"', '"s98"', '"s99"', '"vcc"', '"scc"', '"m0"', '"memory"']
+    if fused:
+        ins.append('[vb] "v"(vb)')
+        clob = [f'"a{i}"' for i in range(256)] + [f'"s{i}"' for i in range(88, 94)] + clob
     with open(path, "w") as f:
-        f.write("// GENERATED by gen_w4_loop.py -- do not edit.  The K-loop of one vocabulary tile (4-wave kernel).\n")
+        f.write("// GENERATED by gen_w4_loop.py -- do not edit.  " +
+                ("One vocabulary tile of the greedy 4-wave kernel: K-loop and vocabulary reduction.\n" if fused else
+                 "The K-loop of one vocabulary tile (4-wave kernel).\n"))
         f.write("asm volatile(\n")
         for ln in lines:
             f.write(f'    "{ln}\\n"\n')
@@ -337,6 +440,13 @@ def main(path):
         f.write("    : " + ",\n      ".join(ins) + "\n")
         f.write("    : " + ", ".join(clob) + ");\n")
     print(f"{path}: {len(lines)} asm lines, {len(outs) + len(ins)} operands")
+
+
+def main(path):
+    write_statement(path, fused=False)
+    write_statement(path.replace("_loop.inc", "_tile.inc"), fused=True)
+    lines.clear()
+    build()          # leave the K-loop listing in `lines` for importers
 
 
 if __name__ == "__main__":

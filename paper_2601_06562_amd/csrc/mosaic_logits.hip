@@ -757,13 +757,6 @@ __global__ __launch_bounds__(256) void masked_logits_kernel_w4(const KernelParam
     }
 
     for (int n = 0; n < ntile; ++n) {
-      f32x4 acc[8][8];
-#pragma unroll
-      for (int bi = 0; bi < 8; ++bi)
-#pragma unroll
-        for (int bj = 0; bj < 8; ++bj)
-#pragma unroll
-          for (int r = 0; r < 4; ++r) acc[bi][bj][r] = 0.f;
       st_wsrc_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)st_wsrc_lo);
       st_wsrc_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)st_wsrc_hi);
       st_hsrc_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)st_hsrc_lo);
@@ -780,14 +773,28 @@ __global__ __launch_bounds__(256) void masked_logits_kernel_w4(const KernelParam
       const uint32_t st_nk = (uint32_t)__builtin_amdgcn_readfirstlane((int)u_nk);
       const uint32_t st_wwrap = (uint32_t)__builtin_amdgcn_readfirstlane((int)u_wwrap);
       const uint32_t st_hwrap = (uint32_t)__builtin_amdgcn_readfirstlane((int)u_hwrap);
-        bf16x8 frag_a[2][8], frag_b[2][8];   // written and consumed inside the loop only
+        bf16x8 frag_a[2][8], frag_b[2][8];   // written and consumed inside the statement only
         uint32_t addr_tmp0, addr_tmp1;
+        const int vb = (vt0 + n) * kTileVocab + wv * 128 + 4 * q;   // vocabulary id of this lane's element 0
+        if constexpr (SAMPLE) {
+          // sampling: the K-loop statement leaves the tile in `acc`; the reduction with the noise is C++
+          f32x4 acc[8][8];
+#pragma unroll
+          for (int bi = 0; bi < 8; ++bi)
+#pragma unroll
+            for (int bj = 0; bj < 8; ++bj)
+#pragma unroll
+              for (int r = 0; r < 4; ++r) acc[bi][bj][r] = 0.f;
 #include "mosaic_w4_loop.inc"
+          reduce_tile16_sample(acc, run_m, run_s, run_ym, run_xa, run_i, vb, pos, p.seed_lo, p.seed_hi, p.tau);
+        } else {
+          // greedy: one statement clears the accumulators (the AGPR file, by number), runs the K-loop and folds
+          // the tile into the running triples, so nothing of it is left to the compiler's scheduling
+          float red_x[32], red_t, red_mn, red_nml, red_y;
+          int red_sel;
+#include "mosaic_w4_tile.inc"
+        }
       }
-      const int v_tile0 = (vt0 + n) * kTileVocab;
-      const int vb = v_tile0 + wv * 128 + 4 * q;
-      if constexpr (SAMPLE) reduce_tile16_sample(acc, run_m, run_s, run_ym, run_xa, run_i, vb, pos, p.seed_lo, p.seed_hi, p.tau);
-      else reduce_tile16(acc, run_m, run_s, run_i, vb);
     }
 
     // Unit end: fold the four lanes that share a token (lane ^ 16, lane ^ 32), then the two waves that
