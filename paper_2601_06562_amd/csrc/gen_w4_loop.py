@@ -48,8 +48,10 @@ def acc_reg(bi, bj, r):
     return f"a{(bi * 8 + bj) * 4 + r}"
 
 
-def mfma(bi, bj, buf):
-    e(f"v_mfma_f32_16x16x32_bf16 {acc_block(bi, bj)}, {FA[buf][bi]}, {FB[buf][bj]}, {acc_block(bi, bj)}")
+def mfma(bi, bj, buf, zero_c=False):
+    """acc += A * B, or acc = A * B (the first product of a tile: no clearing of the accumulator beforehand)"""
+    c = "0" if zero_c else acc_block(bi, bj)
+    e(f"v_mfma_f32_16x16x32_bf16 {acc_block(bi, bj)}, {FA[buf][bi]}, {FB[buf][bj]}, {c}")
 
 
 def read_addr(ks):
@@ -156,7 +158,6 @@ def cond_plus(plus):
 # possible time to land before the sync that publishes it, and four MFMAs apart, so the 16 KiB a workgroup
 # requests per position never queue up behind the texture addresser (denser or later placement measured slower).
 COPY_POS = [1, 5, 9, 13, 17, 21, 25, 29]
-STEADY_UNROLL = 1
 
 
 def spread(fill, first, ops, per_gap=2):
@@ -168,13 +169,13 @@ def spread(fill, first, ops, per_gap=2):
     return k
 
 
-def scheduled_group(buf, fill):
+def scheduled_group(buf, fill, zero_c=False):
     """64 MFMAs on fragment buffer `buf`; fill[k] = the instructions that follow MFMA k.  A wave is alone on its
     SIMD and issues one instruction every few cycles, so whatever sits between two MFMAs beyond ~3 instructions
     delays the second one: the steady state keeps every gap that short."""
     order = [(bi, bj) for bi in range(8) for bj in range(8)]
     for k in range(64):
-        mfma(*order[k], buf)
+        mfma(*order[k], buf, zero_c)
         for x in fill.get(k, []):
             e(x)
 
@@ -318,10 +319,9 @@ def reduce_column(tb):
 
 
 def build_tile():
-    """The statement of the greedy kernel: clear the accumulators, the K-loop, then the reduction of the tile."""
+    """The statement of the greedy kernel: the K-loop on accumulators it starts itself, then the reduction of the
+    tile."""
     LITERAL_ACC[0] = True
-    for i in range(256):
-        e(f"v_accvgpr_write_b32 a{i}, 0")
     build()
     for tb in range(8):
         reduce_column(tb)
@@ -339,6 +339,11 @@ def build():
     read_addr(0)
     for r in reads(0):
         e(r)
+    if LITERAL_ACC[0]:
+        # the statement owns the accumulators: clear them while the first fragments are on their way (measured:
+        # writing a tile's first products without an addend instead saves nothing)
+        for i in range(256):
+            e(f"v_accvgpr_write_b32 a{i}, 0")
     e("s_nop 7")
     top, steady, generic, out = label("top"), label("steady"), label("generic"), label("out")
     e(f"{top}:")
@@ -349,16 +354,12 @@ def build():
     read_addr(1)
     e(f"{steady}:")
     leave = label("leave")
-    for copy in range(STEADY_UNROLL):                        # a taken branch costs more than an MFMA: one per
-        e("s_waitcnt lgkmcnt(0)")                            # STEADY_UNROLL steps
-        scheduled_group(0, steady_fill(0))                   # LM-head tile g+2 goes out
-        e("s_waitcnt vmcnt(8) lgkmcnt(0)")                   # all copies but the LM-head tile just issued; fragments
-        e("s_barrier")
-        scheduled_group(1, steady_fill(1))                   # hidden tile g+2 goes out
-        if copy + 1 < STEADY_UNROLL:
-            e(f"s_cbranch_scc0 {leave}")
-        else:
-            e(f"s_cbranch_scc1 {steady}")
+    e("s_waitcnt lgkmcnt(0)")
+    scheduled_group(0, steady_fill(0))                       # LM-head tile g+2 goes out
+    e("s_waitcnt vmcnt(8) lgkmcnt(0)")                       # all copies but the LM-head tile just issued; fragments
+    e("s_barrier")
+    scheduled_group(1, steady_fill(1))                       # hidden tile g+2 goes out
+    e(f"s_cbranch_scc1 {steady}")
     e(f"{leave}:")
     e(f"s_cmp_lt_u32 {KT}, %[nk]")
     e(f"s_cbranch_scc0 {out}")

@@ -28,13 +28,22 @@ W_BASE, H_BASE = 0x10_0000_0000, 0x20_0000_0000       # synthetic device address
 MASK32 = 0xFFFFFFFF
 
 
-def generated_lines():
+def generated_lines(fused=False):
+    """The K-loop listing: of the statement whose accumulators are operands (the tile is reduced in C++), or, with
+    fused=True, the K-loop part of the statement that owns the accumulators and reduces the tile itself."""
     spec = importlib.util.spec_from_file_location("gen_w4_loop", GEN)
     mod = importlib.util.module_from_spec(spec)
     spec.loader.exec_module(mod)
     mod.lines.clear()
-    mod.build()
-    return list(mod.lines)
+    if fused:
+        mod.build_tile()
+        out = list(mod.lines)
+        out = out[:next(i for i, ln in enumerate(out) if ln.strip().startswith("v_accvgpr_read_b32"))]
+    else:
+        mod.build()
+        out = list(mod.lines)
+    mod.lines.clear()
+    return out
 
 
 class Sim:
@@ -63,6 +72,8 @@ class Sim:
         self.mfma_count = 0
         self.frag_last_group = {}      # fragment register -> last MFMA group that used it
         self.copy_parts = {}           # (slot) -> pieces issued for the current copy (8 instructions per tile per wave)
+        self.started = set()           # accumulator registers (by number) started in the current statement
+        self.literal_acc = False
 
     # ---- operand access
     def val(self, tok):
@@ -151,7 +162,16 @@ class Sim:
         for k, f in self.frag.items():
             self.frag[k] = (f[0], f[1], f[2], True)
 
-    def mfma(self, a, b):
+    def mfma(self, a, b, dst=None, src_c=None):
+        m = re.fullmatch(r"a\[(\d+):(\d+)\]", dst or "")
+        if m:                           # accumulators by number: the statement itself must have started them
+            self.literal_acc = True
+            regs = set(range(int(m.group(1)), int(m.group(2)) + 1))
+            if src_c == "0":
+                assert self.mfma_count % 128 < 64 and not (regs & self.started), "a product without addend mid-tile"
+                self.started |= regs
+            else:
+                assert src_c == dst and regs <= self.started, f"accumulation into {dst}, which was never started"
         group, g, h = self.mfma_count // 64, (self.mfma_count // 64) // 2, (self.mfma_count // 64) % 2
         for name, operand in ((a, "W"), (b, "H")):
             assert name in self.frag, f"{name} used before it was read"
@@ -194,6 +214,7 @@ class Sim:
     def run_statement(self):
         self.frag.clear()                 # fragment registers do not survive between statements
         self.frag_last_group.clear()
+        self.started.clear()              # nor do accumulators the statement addresses by number
         pc, steps = 0, 0
         while pc < len(self.prog):
             steps += 1
@@ -203,7 +224,10 @@ class Sim:
             op, _, rest = ins.partition(" ")
             args = [a.strip() for a in rest.split(",")] if rest else []
             if op == "v_mfma_f32_16x16x32_bf16":
-                self.mfma(args[1], args[2])
+                self.mfma(args[1], args[2], args[0], args[3])
+            elif op == "v_accvgpr_write_b32":
+                assert args[1] == "0" and self.mfma_count % 128 == 0
+                self.started.add(int(args[0][1:]))
             elif op == "ds_read_b128":
                 m = re.fullmatch(r"(\S+)(?: offset:(\d+))?", args[1])
                 self.ds_read(args[0], m.group(1), int(m.group(2) or 0))
@@ -256,9 +280,9 @@ class Sim:
                 raise AssertionError(f"instruction the checker does not know: {ins}")
 
 
-@pytest.fixture(scope="module")
-def lines():
-    return generated_lines()
+@pytest.fixture(scope="module", params=["accumulators as operands", "fused with the reduction"])
+def lines(request):
+    return generated_lines(fused=request.param.startswith("fused"))
 
 
 @pytest.mark.parametrize("nk", [1, 2, 3, 4, 5, 8, 56, 64])
@@ -272,6 +296,7 @@ def test_ring_protocol(lines, nk, ntile):
         sim.run_statement()
     total = nk * ntile
     assert sim.mfma_count == 128 * total                            # every step ran both of its groups
+    assert not sim.literal_acc or sim.started == set(range(256))    # the last statement started all 256 registers
     assert sim.reg["%[g]"] == total
     assert sim.next_w_copy == max(total, 3) and sim.next_h_copy == max(total, 2)   # every tile copied exactly once
     assert not sim.unpublished, "copies still unpublished at the end: a later statement would race with them"
@@ -304,7 +329,7 @@ def test_steady_state_keeps_every_gap_between_mfmas_short(lines):
     whole kernel, the same 16 spread one per gap nothing.  In the steady-state body every gap holds at most two
     instructions, the sync between the two groups of a step two (wait + barrier), and the only branch taken is the
     back edge right behind the last MFMA."""
-    prog = [ln.strip() for ln in lines if ln.strip()]
+    prog = [ln.strip() for ln in lines if ln.strip() and not ln.strip().endswith(":") or ln.strip().startswith(("Lsteady", "Lleave"))]
     start = next(i for i, ln in enumerate(prog) if ln.startswith("Lsteady"))
     end = next(i for i, ln in enumerate(prog) if ln.startswith("Lleave"))
     body = prog[start + 1:end]

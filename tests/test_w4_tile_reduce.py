@@ -135,14 +135,18 @@ def reduction():
     return prog, prog[first:]
 
 
-def test_statement_clears_every_accumulator_and_multiplies_into_them_by_number(reduction):
+def test_statement_addresses_the_accumulators_by_number_and_clears_them_itself(reduction):
+    """Every MFMA accumulates into an aligned block of four AGPRs named by number, and the statement clears all 256
+    registers before its first MFMA (the K-loop checker proves it for every path through the listing)."""
     prog, _ = reduction
-    assert prog[:256] == [f"v_accvgpr_write_b32 a{i}, 0" for i in range(256)]
+    clears = [i for i, ln in enumerate(prog) if ln.startswith("v_accvgpr_write_b32")]
+    assert [prog[i] for i in clears] == [f"v_accvgpr_write_b32 a{i}, 0" for i in range(256)]
+    assert clears[-1] < next(i for i, ln in enumerate(prog) if ln.startswith("v_mfma"))
     blocks = set()
     for ln in prog:
         if ln.startswith("v_mfma"):
             dst, _, _, src_c = [x.strip() for x in ln.split(" ", 1)[1].split(",")]
-            assert dst == src_c and re.fullmatch(r"a\[\d+:\d+\]", dst)
+            assert src_c == dst and re.fullmatch(r"a\[\d+:\d+\]", dst)
             lo, hi = map(int, dst[2:-1].split(":"))
             assert lo % 4 == 0 and hi == lo + 3
             blocks.add(lo // 4)
