@@ -851,33 +851,50 @@ __global__ __launch_bounds__(256) void masked_logits_kernel_w4(const KernelParam
   }
 }
 
-// Merge the S partial results of every row and emit the outputs.  A block handles 16 rows; its 16 thread groups
-// each fold the splits g, g+16, g+32, ... in ascending order and thread group 0 then folds the 16 group results in
-// ascending order, so the order is a function of S alone (run-to-run and chunking-independent results) while a
-// row's chain of dependent loads is S/16 long instead of S (with one row tile spread over ~250 splits the
-// sequential merge took a third of the step).
-constexpr int kCombineRows = 16;
+// Merge the S partial results of every row and emit the outputs.  A block of 256 threads handles ROWS rows with
+// G = 256 / ROWS thread groups: group g folds the splits g, g + G, g + 2G, ... in ascending order (their loads
+// issued together), then the G group results are folded pairwise, group g with group g + stride for stride = G/2,
+// G/4, ..., 1.  The order is a function of S alone (run-to-run and chunking-independent results) and a row's chain
+// of dependent steps is S / G + log2 G long instead of S.  Few splits: 16 rows x 16 groups; many splits (one row
+// tile spread over ~250 of them, where this kernel is a visible part of the step): 4 rows x 64 groups -- the
+// sequential merge took 114 us there, 16 groups with a sequential second level 16 us.
+template <int ROWS>
 __global__ __launch_bounds__(256) void combine_kernel(const KernelParams p) {
-  __shared__ float sh_m[16][kCombineRows], sh_s[16][kCombineRows], sh_ym[16][kCombineRows], sh_xa[16][kCombineRows];
-  __shared__ int sh_i[16][kCombineRows];
+  constexpr int G = 256 / ROWS;
+  constexpr int kPerGroup = (MOSAIC_MAX_VOCAB_SPLITS + G - 1) / G;   // splits one group folds at most
+  __shared__ float sh_m[G][ROWS], sh_s[G][ROWS], sh_ym[G][ROWS], sh_xa[G][ROWS];
+  __shared__ int sh_i[G][ROWS];
   int total = *p.count;
   if (total > p.max_rows) total = p.max_rows;
   int rows = total - p.row0;
   if (rows > p.chunk_rows) rows = p.chunk_rows;
-  const int lr = threadIdx.x & (kCombineRows - 1), g = threadIdx.x >> 4;
-  const int r = blockIdx.x * kCombineRows + lr;
+  const int lr = threadIdx.x % ROWS, g = threadIdx.x / ROWS;
+  const int r = blockIdx.x * ROWS + lr;
   const bool valid = r < rows;
   const bool sample = p.tau > 0.f;   // sampling: the token is the arg-max of the perturbed scores
   float m = kNeg, s = 0.f, ym = kNeg, xa = 0.f;
   int i = INT_MAX;
   if (valid) {
-    for (int sp = g; sp < p.splits; sp += 16) {
-      const int64_t slot = (int64_t)sp * p.c_pad + r;
+    float lm[kPerGroup], ls[kPerGroup], lym[kPerGroup], lxa[kPerGroup];
+    int li[kPerGroup];
+#pragma unroll
+    for (int k = 0; k < kPerGroup; ++k) {
+      const int sp = g + k * G;
+      const bool on = sp < p.splits;
+      const int64_t slot = (int64_t)(on ? sp : 0) * p.c_pad + r;
+      lm[k] = on ? p.part_m[slot] : kNeg;        // beyond S: the neutral element
+      ls[k] = on ? p.part_s[slot] : 0.f;
+      li[k] = on ? p.part_i[slot] : INT_MAX;
+      lym[k] = (on && sample) ? p.part_ym[slot] : kNeg;
+      lxa[k] = (on && sample) ? p.part_xa[slot] : 0.f;
+    }
+#pragma unroll
+    for (int k = 0; k < kPerGroup; ++k) {
       if (sample) {
-        merge_ms(m, s, p.part_m[slot], p.part_s[slot]);
-        merge_pick(ym, xa, i, p.part_ym[slot], p.part_xa[slot], p.part_i[slot]);
+        merge_ms(m, s, lm[k], ls[k]);
+        merge_pick(ym, xa, i, lym[k], lxa[k], li[k]);
       } else {
-        merge_triple(m, s, i, p.part_m[slot], p.part_s[slot], p.part_i[slot]);
+        merge_triple(m, s, i, lm[k], ls[k], li[k]);
       }
     }
   }
@@ -887,20 +904,29 @@ __global__ __launch_bounds__(256) void combine_kernel(const KernelParams p) {
   sh_ym[g][lr] = ym;
   sh_xa[g][lr] = xa;
   __syncthreads();
-  if (g != 0 || !valid) return;
-  const int groups = p.splits < 16 ? p.splits : 16;   // groups beyond S hold the neutral element
-  for (int gg = 1; gg < groups; ++gg) {
-    if (sample) {
-      merge_ms(m, s, sh_m[gg][lr], sh_s[gg][lr]);
-      merge_pick(ym, xa, i, sh_ym[gg][lr], sh_xa[gg][lr], sh_i[gg][lr]);
-    } else {
-      merge_triple(m, s, i, sh_m[gg][lr], sh_s[gg][lr], sh_i[gg][lr]);
+#pragma unroll
+  for (int stride = G / 2; stride >= 1; stride >>= 1) {
+    if (g < stride) {
+      if (sample) {
+        merge_ms(m, s, sh_m[g + stride][lr], sh_s[g + stride][lr]);
+        merge_pick(ym, xa, i, sh_ym[g + stride][lr], sh_xa[g + stride][lr], sh_i[g + stride][lr]);
+      } else {
+        merge_triple(m, s, i, sh_m[g + stride][lr], sh_s[g + stride][lr], sh_i[g + stride][lr]);
+      }
+      sh_m[g][lr] = m;
+      sh_s[g][lr] = s;
+      sh_i[g][lr] = i;
+      sh_ym[g][lr] = ym;
+      sh_xa[g][lr] = xa;
     }
+    __syncthreads();
   }
+  if (g != 0 || !valid) return;
   p.out_token[p.row0 + r] = i;
   p.out_lse[p.row0 + r] = m + __builtin_amdgcn_logf(s) * kLn2;
   p.out_conf[p.row0 + r] = sample ? __builtin_amdgcn_exp2f((xa - m) * kLog2e) / s : 1.0f / s;
 }
+constexpr int kWideMergeSplits = 64;   // from this many splits on, the 64-group merge
 
 int launch_masked_logits(const LogitsArgs& a, const mosaic_plan& plan, hipStream_t stream) {
   KernelParams p;
@@ -985,7 +1011,10 @@ int launch_masked_logits(const LogitsArgs& a, const mosaic_plan& plan, hipStream
       else
         rc |= launch_kernel(masked_logits_kernel<3, 2, false>, dim3((unsigned)tgrid), dim3(kThreads), stream, tail);
     }
-    rc |= launch_kernel(combine_kernel, dim3((unsigned)((cap + kCombineRows - 1) / kCombineRows)), dim3(256), stream, p);
+    if (p.splits >= kWideMergeSplits)
+      rc |= launch_kernel(combine_kernel<4>, dim3((unsigned)((cap + 3) / 4)), dim3(256), stream, p);
+    else
+      rc |= launch_kernel(combine_kernel<16>, dim3((unsigned)((cap + 15) / 16)), dim3(256), stream, p);
     if (rc != 0) break;
   }
   return rc;
