@@ -533,93 +533,10 @@ __global__ __launch_bounds__(kThreads) void masked_logits_kernel(const KernelPar
   }
 }
 
-using f32x4 = __attribute__((ext_vector_type(4))) float;
-
-// Reduction of one finished 256x256 logits tile for the 16x16x32 layout: this lane holds, for each of
-// 8 token columns (tb*16 + lane%16), 8 blocks x 4 vocabulary ids (vb + 16*bi + r).
-__device__ __forceinline__ void reduce_tile16(f32x4 (&acc)[8][8], float (&m)[8], float (&s)[8], int (&ix)[8], int vb) {
-#pragma unroll
-  for (int tb = 0; tb < 8; ++tb) {
-    float x[32];   // this column's 32 logits, read out of the accumulators once
-#pragma unroll
-    for (int bi = 0; bi < 8; ++bi)
-#pragma unroll
-      for (int r = 0; r < 4; ++r) x[bi * 4 + r] = acc[bi][tb][r];
-    float mt = kNeg;
-#pragma unroll
-    for (int e = 0; e < 32; ++e) mt = fmaxf(mt, x[e]);
-    int sel = 0;
-#pragma unroll
-    for (int e = 31; e >= 0; --e) sel = (x[e] == mt) ? ((e >> 2) * 16 + (e & 3)) : sel;  // descending: lowest id wins
-    const bool upd = mt > m[tb];
-    ix[tb] = upd ? vb + sel : ix[tb];
-    const float mn = fmaxf(m[tb], mt);
-    const float nml = -mn * kLog2e;
-    float p0 = 0.f, p1 = 0.f, p2 = 0.f, p3 = 0.f;
-#pragma unroll
-    for (int e = 0; e < 32; e += 4) {
-      p0 += __builtin_amdgcn_exp2f(__builtin_fmaf(x[e + 0], kLog2e, nml));
-      p1 += __builtin_amdgcn_exp2f(__builtin_fmaf(x[e + 1], kLog2e, nml));
-      p2 += __builtin_amdgcn_exp2f(__builtin_fmaf(x[e + 2], kLog2e, nml));
-      p3 += __builtin_amdgcn_exp2f(__builtin_fmaf(x[e + 3], kLog2e, nml));
-    }
-    s[tb] = s[tb] * __builtin_amdgcn_exp2f((m[tb] - mn) * kLog2e) + ((p0 + p1) + (p2 + p3));
-    m[tb] = mn;
-    __builtin_amdgcn_sched_barrier(0);   // one column at a time: keeps the live set at ~40 registers
-  }
-}
-
-// The same column-wise reduction under sampling: also the arg-max of x + tau*g and the plain logit there.
-__device__ __forceinline__ void reduce_tile16_sample(f32x4 (&acc)[8][8], float (&m)[8], float (&s)[8], float (&ym)[8],
-                                                     float (&xa)[8], int (&ix)[8], int vb, const int (&pos)[8],
-                                                     uint32_t k0, uint32_t k1, float tau) {
-#pragma unroll
-  for (int tb = 0; tb < 8; ++tb) {
-    float x[32];
-#pragma unroll
-    for (int bi = 0; bi < 8; ++bi)
-#pragma unroll
-      for (int r = 0; r < 4; ++r) x[bi * 4 + r] = acc[bi][tb][r];
-    float mt = kNeg, yt = kNeg, xsel = 0.f;
-    int sel = 0;
-#pragma unroll
-    for (int bi = 7; bi >= 0; --bi) {
-      float n[4];
-      gumbel4(k0, k1, (uint32_t)pos[tb], (uint32_t)(vb + 16 * bi) >> 2, tau, n);
-#pragma unroll
-      for (int r = 3; r >= 0; --r) {
-        const float xv = x[bi * 4 + r];
-        const float y = xv + n[r];
-        mt = fmaxf(mt, xv);
-        const bool better = y >= yt;   // descending scan: on equal scores the lower id replaces the higher
-        sel = better ? bi * 16 + r : sel;
-        xsel = better ? xv : xsel;
-        yt = better ? y : yt;
-      }
-    }
-    const bool upd = yt > ym[tb];
-    ix[tb] = upd ? vb + sel : ix[tb];
-    xa[tb] = upd ? xsel : xa[tb];
-    ym[tb] = upd ? yt : ym[tb];
-    const float mn = fmaxf(m[tb], mt);
-    const float nml = -mn * kLog2e;
-    float p0 = 0.f, p1 = 0.f, p2 = 0.f, p3 = 0.f;
-#pragma unroll
-    for (int e = 0; e < 32; e += 4) {
-      p0 += __builtin_amdgcn_exp2f(__builtin_fmaf(x[e + 0], kLog2e, nml));
-      p1 += __builtin_amdgcn_exp2f(__builtin_fmaf(x[e + 1], kLog2e, nml));
-      p2 += __builtin_amdgcn_exp2f(__builtin_fmaf(x[e + 2], kLog2e, nml));
-      p3 += __builtin_amdgcn_exp2f(__builtin_fmaf(x[e + 3], kLog2e, nml));
-    }
-    s[tb] = s[tb] * __builtin_amdgcn_exp2f((m[tb] - mn) * kLog2e) + ((p0 + p1) + (p2 + p3));
-    m[tb] = mn;
-    __builtin_amdgcn_sched_barrier(0);
-  }
-}
-
 // ---- 4-wave fast path: one wave per SIMD, 128 (vocab) x 128 (token) per wave as 8 x 8 blocks of
 // v_mfma_f32_16x16x32_bf16 (the more power-efficient bf16 shape on this part), accumulators in AGPRs.
-// The K-loop of a vocabulary tile is one hand-scheduled inline-asm statement (w4_loop.inc, generated):
+// A vocabulary tile is one hand-scheduled inline-asm statement (mosaic_w4_tile.inc greedy, mosaic_w4_tile_sample.inc
+// sampling; both generated): the K-loop, then the tile's reduction into the running per-column state.  In the K-loop
 // every MFMA is followed by at most one LDS read or one direct-to-LDS copy, fragments are double-
 // buffered in fixed VGPRs, the LM-head ring runs two K-tiles ahead and the hidden ring one.
 // Preconditions (checked by the launcher): V % 256 == 0, hidden span < 4 GiB, 256*d*2 < 4 GiB.
@@ -676,6 +593,12 @@ __global__ __launch_bounds__(256) void masked_logits_kernel_w4(const KernelParam
 #pragma unroll
   for (int i = 0; i < 8; ++i) woff[i] = (uint32_t)(drow + 8 * i) * w_row_bytes + ((i & 1) ? chunk_odd : chunk_even);
 
+  // sampling: the generator's key (the statement derives the round keys from it), its multipliers, 1/tau and tau
+  const uint32_t seed_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)p.seed_lo);
+  const uint32_t seed_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)p.seed_hi);
+  const uint32_t philox_m0 = 0xD2511F53u, philox_m1 = 0xCD9E8D57u;
+  const float tau_s = p.tau;
+  const float inv_tau_log2e = SAMPLE ? kLog2e / p.tau : 0.f;
   const uint32_t u_nk = (uint32_t)nk;
   const uint32_t u_wwrap = 256u * w_row_bytes - (uint32_t)(nk - 1) * 128u;
   const uint32_t u_hwrap = (uint32_t)(nk - 1) * 128u;
@@ -773,23 +696,16 @@ __global__ __launch_bounds__(256) void masked_logits_kernel_w4(const KernelParam
       const uint32_t st_nk = (uint32_t)__builtin_amdgcn_readfirstlane((int)u_nk);
       const uint32_t st_wwrap = (uint32_t)__builtin_amdgcn_readfirstlane((int)u_wwrap);
       const uint32_t st_hwrap = (uint32_t)__builtin_amdgcn_readfirstlane((int)u_hwrap);
-        bf16x8 frag_a[2][8], frag_b[2][8];   // written and consumed inside the statement only
         uint32_t addr_tmp0, addr_tmp1;
         const int vb = (vt0 + n) * kTileVocab + wv * 128 + 4 * q;   // vocabulary id of this lane's element 0
         if constexpr (SAMPLE) {
-          // sampling: the K-loop statement leaves the tile in `acc`; the reduction with the noise is C++
-          f32x4 acc[8][8];
-#pragma unroll
-          for (int bi = 0; bi < 8; ++bi)
-#pragma unroll
-            for (int bj = 0; bj < 8; ++bj)
-#pragma unroll
-              for (int r = 0; r < 4; ++r) acc[bi][bj][r] = 0.f;
-#include "mosaic_w4_loop.inc"
-          reduce_tile16_sample(acc, run_m, run_s, run_ym, run_xa, run_i, vb, pos, p.seed_lo, p.seed_hi, p.tau);
+          // sampling: the same, with the Gumbel-max draw in the reduction (fragments, accumulators, the
+          // reduction's temporaries and the round keys all by number)
+#include "mosaic_w4_tile_sample.inc"
         } else {
           // greedy: one statement clears the accumulators (the AGPR file, by number), runs the K-loop and folds
           // the tile into the running triples, so nothing of it is left to the compiler's scheduling
+          bf16x8 frag_a[2][8], frag_b[2][8];   // written and consumed inside the statement only
           float red_x[32], red_t, red_mn, red_nml, red_y;
           int red_sel;
 #include "mosaic_w4_tile.inc"

@@ -28,17 +28,18 @@ W_BASE, H_BASE = 0x10_0000_0000, 0x20_0000_0000       # synthetic device address
 MASK32 = 0xFFFFFFFF
 
 
-def generated_lines(fused=False):
+def generated_lines(fused=False, sample=False):
     """The K-loop listing: of the statement whose accumulators are operands (the tile is reduced in C++), or, with
-    fused=True, the K-loop part of the statement that owns the accumulators and reduces the tile itself."""
+    fused=True, the K-loop part of a statement that owns the accumulators and reduces the tile itself (the greedy
+    one, or with sample=True the sampling one, whose fragment registers are named by number too)."""
     spec = importlib.util.spec_from_file_location("gen_w4_loop", GEN)
     mod = importlib.util.module_from_spec(spec)
     spec.loader.exec_module(mod)
     mod.lines.clear()
     if fused:
-        mod.build_tile()
+        mod.build_tile_sample() if sample else mod.build_tile()
         out = list(mod.lines)
-        out = out[:next(i for i, ln in enumerate(out) if ln.strip().startswith("v_accvgpr_read_b32"))]
+        out = out[:next(i for i, ln in enumerate(out) if ln.strip().startswith(("v_accvgpr_read_b32", "s_mov_b32 s68, %[seed_lo]")))]
     else:
         mod.build()
         out = list(mod.lines)
@@ -148,7 +149,12 @@ class Sim:
         slot = self.slot_of(addr)
         khalf = 1 if (addr % SLOT) % 128 == 64 else 0
         operand = "W" if slot < NW else "H"
-        assert (operand == "W") == dst.startswith("%[fa"), "LM-head fragments come from the LM-head ring"
+        assert (operand == "W") == (addr_reg == "%[vt0]"), "LM-head fragments come from the LM-head ring"
+        if dst.startswith("%["):
+            assert (operand == "W") == dst.startswith("%[fa")
+        else:                             # fragments by number: LM-head tuples first in each buffer of 16
+            first = int(re.fullmatch(r"v\[(\d+):\d+\]", dst).group(1))
+            assert (operand == "W") == (((first - 112) // 4) % 16 < 8)
         assert slot not in self.unpublished, f"read of slot {slot} while a copy into it is not published"
         assert slot in self.published, f"read of slot {slot} that holds nothing"
         assert slot not in self.copies_this_interval
@@ -280,9 +286,10 @@ class Sim:
                 raise AssertionError(f"instruction the checker does not know: {ins}")
 
 
-@pytest.fixture(scope="module", params=["accumulators as operands", "fused with the reduction"])
+@pytest.fixture(scope="module", params=["accumulators as operands", "fused with the reduction",
+                                        "fused with the sampling reduction"])
 def lines(request):
-    return generated_lines(fused=request.param.startswith("fused"))
+    return generated_lines(fused=request.param.startswith("fused"), sample="sampling" in request.param)
 
 
 @pytest.mark.parametrize("nk", [1, 2, 3, 4, 5, 8, 56, 64])
