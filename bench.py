@@ -85,13 +85,16 @@ def main():
         print(json.dumps({"copy_calibration": True, "bytes_read": 1 << 30, "bytes_written": 1 << 30, "launches": 5}))
         return
     sampling = args.temperature > 0
+    SAMPLING_SEED = 20260106
     traffic_db = {}
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(tpath):
         traffic_db = json.load(open(tpath))
 
-    def measure(name, steps, warmup, budget=0, graph=False):
+    def measure(name, steps, warmup, budget=0, graph=False, temperature=None):
         """One workload: K timed steps on the current stream.  Returns the record and what the oracle check needs."""
+        temperature = args.temperature if temperature is None else temperature
+        sampling = temperature > 0
         wl = workloads.make(name, device=dev)
         M = wl.M
         torch.cuda.synchronize()
@@ -105,9 +108,9 @@ def main():
             if ev is not None:
                 ev[0].record(stream)
             if sampling:
-                binding.mosaic_masked_logits_sample(wl.hidden, wl.w, op.idx, op.count, op.max_rows, args.temperature,
-                                                    20260106 + k, op.token, op.conf, op.lse, op.plan, op.workspace,
-                                                    stream)
+                binding.mosaic_masked_logits_sample(wl.hidden, wl.w, op.idx, op.count, op.max_rows, temperature,
+                                                    SAMPLING_SEED + k, op.token, op.conf, op.lse, op.plan,
+                                                    op.workspace, stream)
             else:
                 binding.mosaic_masked_logits_reduce(wl.hidden, wl.w, op.idx, op.count, op.max_rows, op.token, op.conf,
                                                     op.lse, op.plan, op.workspace, stream)
@@ -179,7 +182,48 @@ def main():
             "logits_bytes_avoided": {"fp32_MxV": 4 * M * wl.V, "fp32_TxV": 4 * wl.T * wl.V},
             "roofline": roof,
         }
+        if sampling:
+            out["last_seed"] = SAMPLING_SEED + steps - 1
         return out, wl, op
+
+    def sampling_check(wl, op, rows_wanted, tau, seed):
+        """The draws of the last timed step against the oracle's Gumbel-max draw on a sample of rows: the same token
+        wherever the oracle's two best perturbed scores are further apart than fp32 rounding can move them, else a
+        token whose perturbed score is within that margin of the best."""
+        import oracle
+        M = wl.M
+        rows = np.unique(np.random.default_rng(1).integers(0, M, rows_wanted))
+        idx_host = op.idx[:M].cpu().numpy()
+        pos = idx_host[rows].astype(np.int64)
+        h_bits = workloads.bf16_bits(wl.hidden[torch.as_tensor(pos, device=dev)])
+        w_bits = workloads.bf16_bits(wl.w)
+        _, logits = oracle.positions(h_bits, w_bits, np.arange(rows.size), return_logits=True)
+        tok = op.token[:M].cpu().numpy()[rows]
+        lse = op.lse[:M].cpu().numpy()[rows].astype(np.float64)
+        conf = op.conf[:M].cpu().numpy()[rows].astype(np.float64)
+        margin = 1e-3 * (1.0 + tau)
+        strict = equal = 0
+        ok = True
+        worst_lse = worst_conf = 0.0
+        for k in range(rows.size):
+            tok_o, conf_o, lse_o, gap_o = oracle.row_sample(logits[k], tau, seed, int(pos[k]))
+            worst_lse = max(worst_lse, abs(lse[k] - lse_o))
+            if not 0 <= tok[k] < wl.V:
+                ok = False
+                continue
+            if tok[k] == tok_o:
+                equal += 1
+                worst_conf = max(worst_conf, abs(conf[k] - conf_o))
+            if gap_o > margin:
+                strict += 1
+                ok = ok and tok[k] == tok_o
+            elif tok[k] != tok_o:
+                y_pick = float(logits[k][tok[k]]) + tau * oracle.gumbel(seed, int(pos[k]), int(tok[k]))
+                y_best = float(logits[k][tok_o]) + tau * oracle.gumbel(seed, int(pos[k]), tok_o)
+                ok = ok and y_pick >= y_best - margin
+        ok = ok and worst_lse <= LSE_ATOL and worst_conf <= CONF_ATOL
+        return {"rows": int(rows.size), "strict_rows": strict, "tokens_equal": equal, "max_abs_dlse": worst_lse,
+                "max_abs_dconf_where_equal": worst_conf, "ok": bool(ok)}
 
     def oracle_check(wl, op, rows_wanted, with_logits=True):
         """Oracle on a stratified sample of the masked rows; the acceptance rule of the parity tests."""
@@ -308,6 +352,22 @@ def main():
             del wl_i, op_i
             torch.cuda.empty_cache()
         out["workloads"] = arr
+        # the sampling variant of the fused kernel (Gumbel-max at temperature 1) on the headline workload, beside
+        # the greedy kernel of this same run
+        steps = max(5, min(args.steps, 20))
+        rec, wl_s, op_s = measure(args.workload, steps, min(args.warmup, 3), budget=args.budget_bytes, temperature=1.0)
+        out["sampling"] = {
+            "workload": args.workload, "temperature": 1.0, "steps": steps, "kernel": rec["roofline"]["kernel"],
+            "kernel_ms": rec["kernel_ms"], "greedy_kernel_ms": head["kernel_ms"],
+            "ratio_to_greedy": rec["kernel_ms"] / head["kernel_ms"],
+            "frac_of_bf16_mfma_peak": rec["roofline"]["frac"] if rec["roofline"]["bound"] == "mfma" else None,
+            "peak_workspace_bytes": rec["peak_workspace_bytes"]}
+        if not args.no_cpu_baseline:
+            out["sampling"]["oracle_check"] = sampling_check(wl_s, op_s, min(args.sample_rows, 64), 1.0,
+                                                             rec["last_seed"])
+            if not out["sampling"]["oracle_check"]["ok"]:
+                failed.append(args.workload + " (sampling)")
+        del wl_s, op_s
     out["parity_failed"] = failed
     print(json.dumps(out), flush=True)
     if failed:
