@@ -48,8 +48,8 @@ def test_every_row_under_sampling():
     M = out["M"]
     w_bits = workloads.bf16_bits(wl.w)
     strict = 0
-    for r0 in range(0, M, 512):
-        rows = np.arange(r0, min(M, r0 + 512))
+    for r0 in range(0, M, 128):
+        rows = np.arange(r0, min(M, r0 + 128))
         hb = workloads.bf16_bits(wl.hidden[torch.as_tensor(out["idx"][rows].astype(np.int64), device=DEV)])
         strict += check_sample(out, hb, w_bits, rows, tau, seed, "llada_first_step sampling")
         print(f"exhaustive sampling: {rows[-1] + 1}/{M} rows", flush=True)
