@@ -272,12 +272,18 @@ int mosaic_mfma_probe(const void *operands, float *sink, int32_t iters, int32_t 
  *                         must be the current device of the calling thread for every later call on the object.
  *                         UNSUPPORTED_SHAPE if the device has no virtual memory management.
  *   mosaic_vmm_resize     makes exactly `bytes`, rounded up to the granularity, of the range usable.  A call
- *                         that changes the rounded size waits for the device to be idle (hipDeviceSynchronize
- *                         -- the only call of this library that does), drops the old mapping and maps new
- *                         pages at the same address: the contents do NOT survive it.  A call that does not
- *                         change it does nothing.  WORKSPACE_TOO_SMALL if bytes exceeds the reservation (nothing
- *                         changes); HIP if the driver refuses, e.g. out of memory (the range is then left with
- *                         nothing mapped: committed_bytes() == 0).
+ *                         that does not change the rounded size does nothing.  Growth first tries to map further
+ *                         pages behind the ones already there: no wait, the contents stay, and if the device has
+ *                         no memory left the call returns HIP with the old pages still mapped.  If the driver
+ *                         refuses that for another reason, and for a shrink or a first mapping, the call waits
+ *                         for the device to be idle (hipDeviceSynchronize -- the only call of this library that
+ *                         does), drops the old mapping and maps new pages at the same address: the contents do
+ *                         NOT survive that; HIP if the driver refuses, e.g. out of memory (the range is then left
+ *                         with nothing mapped: committed_bytes() == 0).  WORKSPACE_TOO_SMALL if bytes exceeds the
+ *                         reservation (nothing changes).
+ *   mosaic_vmm_kept_contents  nonzero if the last resize that changed the size kept what the range held (1: the
+ *                         driver opened the whole mapped prefix in one call, 2: it refused that and opened the
+ *                         new pages alone), else 0.
  *   mosaic_vmm_ptr        device pointer to the start of the range (granularity-aligned); only the first
  *                         mosaic_vmm_committed_bytes() bytes may be touched -- beyond them is unmapped
  *                         address space and an access faults.
@@ -293,6 +299,7 @@ void *mosaic_vmm_ptr(const mosaic_vmm *v);
 int64_t mosaic_vmm_committed_bytes(const mosaic_vmm *v);
 int64_t mosaic_vmm_reserved_bytes(const mosaic_vmm *v);
 int64_t mosaic_vmm_granularity(const mosaic_vmm *v);
+int mosaic_vmm_kept_contents(const mosaic_vmm *v);
 /* Name of the driver call behind the most recent MOSAIC_ERR_HIP of mosaic_vmm_resize ("" if none) and, if
  * hip_error is not NULL, its hipError_t value.  Static storage. */
 const char *mosaic_vmm_last_error(const mosaic_vmm *v, int *hip_error);

@@ -35,7 +35,8 @@ EXPORTS = (
     "mosaic_masked_logits_sample",
     "mosaic_unmask_topn", "mosaic_shift_indices", "mosaic_mfma_probe_flops", "mosaic_mfma_probe", "mosaic_version",
     "mosaic_vmm_create", "mosaic_vmm_resize", "mosaic_vmm_ptr", "mosaic_vmm_committed_bytes",
-    "mosaic_vmm_reserved_bytes", "mosaic_vmm_granularity", "mosaic_vmm_last_error", "mosaic_vmm_destroy",
+    "mosaic_vmm_reserved_bytes", "mosaic_vmm_granularity", "mosaic_vmm_kept_contents", "mosaic_vmm_last_error",
+    "mosaic_vmm_destroy",
 )
 GRAPH_EXPORTS = (
     "mosaic_graph_create", "mosaic_graph_destroy", "mosaic_graph_add_dim", "mosaic_graph_add_chunk_param",
@@ -129,6 +130,8 @@ def lib():
         for name in ("mosaic_vmm_committed_bytes", "mosaic_vmm_reserved_bytes", "mosaic_vmm_granularity"):
             getattr(L, name).restype = i64
             getattr(L, name).argtypes = [p]
+        L.mosaic_vmm_kept_contents.restype = ctypes.c_int
+        L.mosaic_vmm_kept_contents.argtypes = [p]
         L.mosaic_vmm_last_error.restype = ctypes.c_char_p
         L.mosaic_vmm_last_error.argtypes = [p, ctypes.POINTER(ctypes.c_int)]
         L.mosaic_vmm_destroy.restype = ctypes.c_int
@@ -338,6 +341,12 @@ class VmmWorkspace:
     @property
     def granularity(self) -> int:
         return int(lib().mosaic_vmm_granularity(self._h))
+
+    @property
+    def kept_contents(self) -> int:
+        """Nonzero if the last resize that changed the size kept what the range held (growth in place): 1 or 2,
+        by which of its two access calls the driver accepted."""
+        return int(lib().mosaic_vmm_kept_contents(self._h))
 
     def tensor(self, offset, count, dtype):
         """A torch view of `count` elements of `dtype` at byte `offset` of the mapped prefix (no copy, no ownership:

@@ -248,7 +248,7 @@ def test_vmm_entry_points_validate_their_arguments():
     assert L.mosaic_vmm_resize(None, 10) == binding.MOSAIC_ERR_INVALID_ARG
     assert L.mosaic_vmm_ptr(None) is None
     assert L.mosaic_vmm_committed_bytes(None) == 0 and L.mosaic_vmm_reserved_bytes(None) == 0
-    assert L.mosaic_vmm_granularity(None) == 0
+    assert L.mosaic_vmm_granularity(None) == 0 and L.mosaic_vmm_kept_contents(None) == 0
     assert L.mosaic_vmm_destroy(None) == binding.MOSAIC_OK
 
 
