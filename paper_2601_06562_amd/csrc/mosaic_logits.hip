@@ -261,11 +261,12 @@ __device__ __forceinline__ void reduce_tile_sample(f32x16 (&acc)[4][2], float (&
         gumbel4(k0, k1, (uint32_t)pos[bj], (uint32_t)(vb + code0) >> 2, tau, n);
 #pragma unroll
         for (int r = 3; r >= 0; --r) {
-          float x = acc[bi][bj][4 * r4 + r];
-          if (TAIL) {
-            if (vb + code0 + r >= V) { x = kNeg; acc[bi][bj][4 * r4 + r] = kNeg; }
-          }
-          const float y = (TAIL && vb + code0 + r >= V) ? kNeg : x + n[r];
+          // ids past the vocabulary: selects, not branches (a branch per element makes the compiler move whole
+          // accumulator vectors through scratch)
+          const bool past = TAIL && vb + code0 + r >= V;
+          const float x = past ? kNeg : acc[bi][bj][4 * r4 + r];
+          if (TAIL) acc[bi][bj][4 * r4 + r] = x;
+          const float y = past ? kNeg : x + n[r];
           mt = fmaxf(mt, x);
           const bool better = y >= yt;   // descending scan: on equal scores the lower id replaces the higher
           sel = better ? code0 + r : sel;
