@@ -102,6 +102,27 @@ def test_sample_small_shapes_vs_oracle(T, d, V, p, tau):
     assert np.all(out["tok"][M:] == -7) and np.all(out["lse"][M:] == -7.0)
 
 
+@pytest.mark.parametrize("tau", [0.02, 20.0])
+def test_sample_extreme_temperatures(tau):
+    """A hot temperature makes every id a candidate in every tile (the reduction scores whole quads throughout), a cold
+    one nearly none (the draw is the arg-max unless two logits are within a few tau): both ends of the bound."""
+    print(f"sample extreme tau={tau}", flush=True)
+    T, d, V = 1000, 320, 2560
+    wl = workloads.small_random(T, d, V, p=0.6, seed=77, device=DEV)
+    seed = 0xC0FFEE1234567
+    out = run_sample(wl, tau, seed)
+    M = out["M"]
+    rows = np.unique(np.concatenate([np.arange(0, M, 2), np.arange(M - 40, M)]))
+    hb = workloads.bf16_bits(wl.hidden[torch.as_tensor(out["idx"][rows].astype(np.int64), device=DEV)])
+    n_strict = check_sample(out, hb, workloads.bf16_bits(wl.w), rows, tau, seed, f"extreme tau {tau}")
+    assert n_strict >= 0.8 * rows.size
+    if tau < 0.1:        # cold: the draw is the greedy token except on rows whose two largest logits nearly tie
+        op = binding.MaskOnlyLogits(T, d, V, device=DEV)
+        op.step(wl.hidden, wl.w, wl.mask)
+        torch.cuda.synchronize()
+        assert (out["tok"][:M] == op.token.cpu().numpy()[:M]).mean() > 0.7
+
+
 def test_zero_temperature_is_the_greedy_entry_point():
     print("sample tau=0", flush=True)
     for (T, d, V) in [(700, 192, 777), (1000, 320, 1280)]:
