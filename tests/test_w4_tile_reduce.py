@@ -367,9 +367,9 @@ def sampling():
     return split_reduction(tile_listing(sample=True))
 
 
-def sampling_wave(red, agpr, m0, s0, ym0, xa0, i0, pos, vb, seed, tau, force_exact=False):
+def sampling_wave(red, agpr, m0, s0, ym0, xa0, i0, pos, vb, seed, tau, force_exact=False, mutate=None):
     n = agpr.shape[1]
-    prog = list(red)
+    prog = list(red) if mutate is None else mutate(list(red))
     if force_exact:      # every id takes the exact path: the bound on the words is dropped
         wlo = TEMPS["wlo"]
         hits = [k for k, ln in enumerate(prog) if ln == f"v_lshlrev_b32 {wlo}, 9, {wlo}"]
@@ -465,3 +465,32 @@ def test_sampling_reduction_draws_what_the_oracle_draws_and_skips_only_losers(sa
     early = sampling_wave(sampling, flat, m0, s0, np.full((8, n), 3.0 + 5.0 * tau, np.float32), xa0, i0, pos, vb, seed, tau)
     assert early.slow_taken >= 24 and early.flushes <= early.slow_taken // 4 and early.fulls <= early.flushes // 2, \
         (early.slow_taken, early.flushes, early.fulls)
+
+
+def test_a_queue_that_forgets_to_score_before_refilling_is_caught(sampling):
+    """Planted mistake: the jump that scores a lane's queue before a second candidate is filed is dropped, so the second
+    candidate overwrites the first.  With nothing bounding the scores (a fresh row: every id is a candidate) the
+    draw must then differ from the exact one, which is what the comparison above relies on."""
+    rng = np.random.default_rng(5)
+    n, seed, tau = 64, 0xDEADBEEF12345678, 1.0
+    agpr = planted_tile(rng, n)
+    lane = np.arange(n, dtype=np.uint32)
+    vb = np.full(n, 9 * 256, np.uint32) + 4 * (lane >> 4)
+    pos = [rng.integers(0, 4096, 16).astype(np.uint32)[lane % 16] for _ in range(8)]
+    m0, s0 = running_state(rng, agpr, n)
+    i0 = (300000 + rng.permutation(8 * n).reshape(8, n)).astype(np.uint32)
+    xa0 = rng.standard_normal((8, n)).astype(np.float32)
+    ym0 = np.full((8, n), -1.0e30, np.float32)
+
+    def drop_flush(prog):
+        hits = [k for k, ln in enumerate(prog) if ln.startswith("s_cbranch_vccnz Lflush")]
+        assert len(hits) == 64
+        for k in hits:
+            prog[k] = "s_nop 0"
+        return prog
+    good = sampling_wave(sampling, agpr, m0, s0, ym0, xa0, i0, pos, vb, seed, tau)
+    exact = sampling_wave(sampling, agpr, m0, s0, ym0, xa0, i0, pos, vb, seed, tau, force_exact=True)
+    bad = sampling_wave(sampling, agpr, m0, s0, ym0, xa0, i0, pos, vb, seed, tau, mutate=drop_flush)
+    assert good.fulls == 64 and bad.fulls == 0
+    assert all(token_level(good, tb) == token_level(exact, tb) for tb in range(8))
+    assert sum(token_level(bad, tb) != token_level(exact, tb) for tb in range(8)) >= 6
