@@ -167,3 +167,40 @@ def test_dream_shape_shifted_prediction_and_sampling():
             assert abs(float(conf[j]) - conf_o) <= 2e-3 and abs(float(conf[j]) - conf_o) <= 5e-3 * max(conf_o, 1e-30)
     assert strict >= 0.9 * len(rows)
     print(f"{name} shifted + sampling: {strict} strict rows of {len(rows)}", flush=True)
+
+
+def test_batched_workload_under_sampling_in_several_rounds():
+    """The batched workload under sampling: 229 row tiles, every workgroup takes 17 units one after the other (the
+    running best, the bound on the generator's words and the candidate queues start afresh in each), rows of every
+    sequence checked against the oracle's draw."""
+    import oracle
+    from paper_2601_06562_amd import binding
+    name = "batched_mixed"
+    print(f"{name}: sampling, generating", flush=True)
+    wl = workloads.make(name, device=DEV)
+    M = wl.M
+    op = binding.MaskOnlyLogits(wl.T, wl.d, wl.V, max_rows=M, device=DEV, sampling=True)
+    assert ((M + 255) // 256) * op.plan.vocab_splits > 4 * op.plan.grid
+    tau, seed = 1.0, 0xABCDEF0123
+    op.sample_step(wl.hidden, wl.w, wl.mask, tau, seed)
+    torch.cuda.synchronize()
+    assert int(op.count.item()) == M
+    idx = op.idx[:M].cpu().numpy()
+    tok, conf, lse = op.token[:M].cpu().numpy(), op.conf[:M].cpu().numpy(), op.lse[:M].cpu().numpy()
+    assert np.all((tok >= 0) & (tok < wl.V)) and np.all(np.isfinite(lse)) and np.all((conf > 0) & (conf <= 1.0 + 1e-6))
+    bounds = np.searchsorted(idx, np.arange(0, wl.T + 1, 16384))
+    extra = []
+    for b in range(8):
+        extra += [int(bounds[b]), int(bounds[b + 1]) - 1, int((bounds[b] + bounds[b + 1]) // 2)]
+    rows = sample_rows(M, np.random.default_rng(29), extra=extra)
+    want, logits = oracle_rows(wl.hidden, workloads.bf16_bits(wl.w), idx[rows], return_logits=True)
+    strict = 0
+    for k, j in enumerate(rows):
+        tok_o, conf_o, lse_o, gap_o = oracle.row_sample(logits[k], tau, seed, int(idx[j]))
+        assert abs(float(lse[j]) - lse_o) <= 2e-3
+        if gap_o > 1e-3 * (1 + tau):
+            strict += 1
+            assert int(tok[j]) == tok_o, (j, int(tok[j]), tok_o, gap_o)
+            assert abs(float(conf[j]) - conf_o) <= 2e-3 and abs(float(conf[j]) - conf_o) <= 5e-3 * max(conf_o, 1e-30)
+    assert strict >= 0.9 * len(rows)
+    print(f"{name} sampling: {strict} strict rows of {len(rows)}", flush=True)
