@@ -56,7 +56,8 @@ const char *mosaic_status_string(int status);
 #define MOSAIC_VOCAB_TILE 256
 #define MOSAIC_K_TILE 64
 #define MOSAIC_MAX_VOCAB_SPLITS 256
-/* Bytes at the end of every workspace for the round counters of the persistent grid (see mosaic_plan_workspace). */
+/* Bytes at the end of every workspace for the round counters of the persistent grid (see mosaic_plan_workspace);
+ * the last word is the flag of the device-side check described at MOSAIC_PLAN_GENERAL_KERNEL. */
 #define MOSAIC_SYNC_BYTES 1024
 
 /* Result of the chunk-size selector.  All fields are filled by mosaic_plan_workspace;
@@ -72,8 +73,10 @@ typedef struct {
 } mosaic_plan;
 
 /* plan.flags bit: use the general 8-wave kernel even where the hand-scheduled 4-wave kernel applies
- * (it applies when V is a multiple of MOSAIC_VOCAB_TILE and hidden spans less than 4 GiB).  Both give
- * the same results; the flag exists for testing and tuning. */
+ * (it applies to the whole tiles of the vocabulary; in a hidden tensor of 4 GiB or more it needs every 64
+ * consecutive rows of the gather list to lie less than 4 GiB apart, which a small kernel checks on the device
+ * before the launch, handing lists with such a gap to the general kernel).  Both give the same results; the flag
+ * exists for testing and tuning. */
 #define MOSAIC_PLAN_GENERAL_KERNEL 1
 /* plan.flags bit, set by the selector: the plan was sized for a sampling step (20 bytes per row and
  * vocabulary split in workspace_bytes instead of 12). */

@@ -50,6 +50,8 @@ int launch_masked_logits(const LogitsArgs& a, const mosaic_plan& plan, hipStream
 struct KernelChoice {
   bool fast;     // 4-wave kernel alone
   bool paired;   // 4-wave kernel + general kernel on the ragged last vocabulary tile
+  bool wide;     // hidden tensor of 4 GiB or more: the 4-wave launch(es) run only where every 64 consecutive rows of
+                 // the list lie less than 4 GiB apart (checked on the device); else the general kernel does the work
 };
 KernelChoice choose_kernel(int64_t T, int64_t ld_h, int32_t d, int32_t V, const mosaic_plan& plan);
 // Name(s) of the kernel(s) launch_masked_logits picks for these sizes and this plan (static storage).

@@ -84,6 +84,12 @@ struct KernelParams {
   float* part_xa;   // the unperturbed logit at that arg-max
   int32_t* sync;    // round counters of the persistent grid (cleared before the launch), sync_slots of them
   int32_t sync_slots;
+  // Hidden tensors of 4 GiB or more.  The 4-wave kernel addresses a wave's 64 rows by 32-bit offsets from the lowest of
+  // them, which works unless those rows lie 4 GiB or more apart; a small kernel looks for such a group in the list
+  // and raises *wide_flag, and of the two launches that follow (4-wave kernel, general kernel) the one whose
+  // wide_run_if differs from the flag returns at once.  nullptr: no such check (the launch always runs).
+  const int32_t* wide_flag;
+  int32_t wide_run_if;
 };
 
 // (m, s, i) monoid: max, sum of exp relative to the max, lowest index attaining the max.
@@ -176,6 +182,34 @@ __device__ __forceinline__ void meet_before_round(const KernelParams& p, int rou
 
 __global__ __launch_bounds__(256) void clear_round_counters_kernel(int32_t* sync, int n) {
   if ((int)threadIdx.x < n) sync[threadIdx.x] = 0;
+}
+
+// For hidden tensors of 4 GiB or more: raises *flag when some group of 64 consecutive rows of the chunk's list (the
+// rows one wave of the 4-wave kernel copies, the last group padded with the last row as that kernel does) spans
+// rows whose byte offsets differ by 4 GiB or more.  One wave per group.
+__global__ __launch_bounds__(256) void span_check_kernel(const int32_t* idx, const int32_t* count, int32_t row0,
+                                                         int32_t chunk_rows, int32_t max_rows, int32_t T,
+                                                         int64_t ldh_bytes, int32_t* flag) {
+  int total = *count;
+  if (total > max_rows) total = max_rows;
+  int rows = total - row0;
+  if (rows > chunk_rows) rows = chunk_rows;
+  const int group = (int)blockIdx.x * 4 + ((int)threadIdx.x >> 6);
+  if (rows <= 0 || group * 64 >= rows) return;
+  int j = group * 64 + ((int)threadIdx.x & 63);
+  if (j > rows - 1) j = rows - 1;
+  int t = idx[row0 + j];
+  t = t < 0 ? 0 : (t > T - 1 ? T - 1 : t);
+  int lo = t, hi = t;
+#pragma unroll
+  for (int x = 32; x >= 1; x >>= 1) {
+    const int a = __shfl_xor(lo, x, 64), b = __shfl_xor(hi, x, 64);
+    lo = a < lo ? a : lo;
+    hi = b > hi ? b : hi;
+  }
+  // the offset of a row from the group's lowest, plus the 16-byte chunk inside the row's K-tile, must fit 32 bits
+  if (((int)threadIdx.x & 63) == 0 && (uint64_t)(hi - lo) * (uint64_t)ldh_bytes >= ((uint64_t)1 << 32) - 256)
+    atomicOr(flag, 1);
 }
 
 template <int N>
@@ -321,6 +355,7 @@ __global__ __launch_bounds__(kThreads) void masked_logits_kernel(const KernelPar
   const int wt = wave >> 1;  // token quarter of the tile
   const int l32 = lane & 31, lhalf = lane >> 5;
 
+  if (p.wide_flag != nullptr && *p.wide_flag != p.wide_run_if) return;   // the other kernel of the two serves this list
   int total = *p.count;
   if (total > p.max_rows) total = p.max_rows;
   int rows = total - p.row0;
@@ -540,7 +575,8 @@ __global__ __launch_bounds__(kThreads) void masked_logits_kernel(const KernelPar
 // sampling; both generated): the K-loop, then the tile's reduction into the running per-column state.  In the K-loop
 // every MFMA is followed by at most one LDS read or one direct-to-LDS copy, fragments are double-
 // buffered in fixed VGPRs, the LM-head ring runs two K-tiles ahead and the hidden ring one.
-// Preconditions (checked by the launcher): V % 256 == 0, hidden span < 4 GiB, 256*d*2 < 4 GiB.
+// Preconditions (checked by the launcher): V % 256 == 0, 256*d*2 < 4 GiB; and, in a hidden tensor of 4 GiB or more,
+// no 64 consecutive rows of the list 4 GiB apart (checked on the device, see KernelParams::wide_flag).
 template <bool SAMPLE>
 __global__ __launch_bounds__(256) void masked_logits_kernel_w4(const KernelParams p) {
   constexpr int NW = 3, NH = 2;
@@ -560,6 +596,7 @@ __global__ __launch_bounds__(256) void masked_logits_kernel_w4(const KernelParam
   const int wt = wave >> 1;  // token half of the tile
   const int l16 = lane & 15, q = lane >> 4;   // MFMA 16x16x32: row/column lane%16, k group lane/16
 
+  if (p.wide_flag != nullptr && *p.wide_flag != p.wide_run_if) return;   // the other kernel of the two serves this list
   int total = *p.count;
   if (total > p.max_rows) total = p.max_rows;
   int rows = total - p.row0;
@@ -619,17 +656,31 @@ __global__ __launch_bounds__(256) void masked_logits_kernel_w4(const KernelParam
     const int total_steps = ntile * nk;
     const uint32_t u_total = (uint32_t)total_steps;
 
-    // Gather: 32-bit byte offsets of the 8 hidden rows this lane copies (rows past the end of the chunk
-    // re-read the last valid row; their results are never stored).
-    uint32_t hoff[8];
+    // Gather: 32-bit byte offsets of the 8 hidden rows this lane copies, from the lowest of the 64 rows this wave
+    // copies (rows past the end of the chunk re-read the last valid row; their results are never stored).  The
+    // offsets fit 32 bits when the hidden tensor is smaller than 4 GiB, and otherwise because this launch only
+    // runs when no wave's rows lie that far apart (span_check_kernel).
+    int trow[8], tmin = INT_MAX;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       int j = tt * kTileRows + drow + 8 * i;
       if (j > rows - 1) j = rows - 1;
       int t = p.idx[p.row0 + j];
       t = t < 0 ? 0 : (t > p.T - 1 ? p.T - 1 : t);   // a bad entry of a caller-built list reads a valid row
-      hoff[i] = (uint32_t)t * (uint32_t)p.ldh_bytes + ((i & 1) ? chunk_odd : chunk_even);
+      trow[i] = t;
+      tmin = t < tmin ? t : tmin;
     }
+#pragma unroll
+    for (int x = 32; x >= 1; x >>= 1) {
+      const int other = __shfl_xor(tmin, x, 64);
+      tmin = other < tmin ? other : tmin;
+    }
+    tmin = __builtin_amdgcn_readfirstlane(tmin);
+    const char* hidden_wave = p.hidden + (int64_t)tmin * p.ldh_bytes;
+    uint32_t hoff[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      hoff[i] = (uint32_t)(trow[i] - tmin) * (uint32_t)p.ldh_bytes + ((i & 1) ? chunk_odd : chunk_even);
 
     // Prologue copies, in this order: W0, H0, W1, W2, H1 (tile 0 is needed first, H1 at the first sync).
     auto copy_w = [&](int gw) {
@@ -640,7 +691,7 @@ __global__ __launch_bounds__(256) void masked_logits_kernel_w4(const KernelParam
         __builtin_amdgcn_global_load_lds((gbl_ptr_t)(src + woff[i]), (lds_ptr_t)(dst + i * 1024), 16, 0, 0);
     };
     auto copy_h = [&](int gh) {
-      const char* src = p.hidden + (gh % nk) * kRowBytes;
+      const char* src = hidden_wave + (gh % nk) * kRowBytes;
       char* dst = smem + (NW + gh % NH) * kOperandBytes + wave_dst;
 #pragma unroll
       for (int i = 0; i < 8; ++i)
@@ -659,7 +710,7 @@ __global__ __launch_bounds__(256) void masked_logits_kernel_w4(const KernelParam
     // State of the asm loop: next tiles to copy are W(3) and H(2) (never issued if past the end).
     const int gw = 3, gh = 2;
     const uint64_t wsrc0 = (uint64_t)(p.w + ((int64_t)(vt0 + gw / nk) * kTileVocab) * (int64_t)w_row_bytes + (gw % nk) * kRowBytes);
-    const uint64_t hsrc0 = (uint64_t)(p.hidden + (gh % nk) * kRowBytes);
+    const uint64_t hsrc0 = (uint64_t)(hidden_wave + (gh % nk) * kRowBytes);
     uint32_t st_wsrc_lo = (uint32_t)wsrc0, st_wsrc_hi = (uint32_t)(wsrc0 >> 32);
     uint32_t st_hsrc_lo = (uint32_t)hsrc0, st_hsrc_hi = (uint32_t)(hsrc0 >> 32);
     uint32_t st_wrd = 0, st_hrd = 0;
@@ -877,13 +928,16 @@ int launch_masked_logits(const LogitsArgs& a, const mosaic_plan& plan, hipStream
   p.part_ym = reinterpret_cast<float*>(p.part_i + (int64_t)plan.vocab_splits * plan.rows_per_chunk);
   p.part_xa = p.part_ym + (int64_t)plan.vocab_splits * plan.rows_per_chunk;
   // the round counters sit behind the partial planes (three for a greedy pass, five for a sampling one)
-  constexpr int kSyncSlots = MOSAIC_SYNC_BYTES / 4;
+  constexpr int kSyncSlots = MOSAIC_SYNC_BYTES / 4 - 1;   // the last word is the flag of the span check
   p.sync = reinterpret_cast<int32_t*>(sample ? p.part_xa + (int64_t)plan.vocab_splits * plan.rows_per_chunk
                                              : p.part_ym);
   p.sync_slots = kSyncSlots;
+  p.wide_flag = nullptr;
+  p.wide_run_if = 0;
 
   const KernelChoice choice = choose_kernel(a.T, a.ld_h, a.d, a.V, plan);
-  const bool fast = choice.fast, paired = choice.paired;
+  const bool fast = choice.fast, paired = choice.paired, wide = choice.wide;
+  int32_t* const flag = p.sync + kSyncSlots;
   // The selector gives a ragged vocabulary one split more than fills the chip (for the pair's second launch);
   // the general kernel alone works best without it.
   if (!fast && !paired && a.V % kTileVocab != 0 && p.vocab_tiles >= 2 && p.splits >= 2) p.splits -= 1;
@@ -900,6 +954,13 @@ int launch_masked_logits(const LogitsArgs& a, const mosaic_plan& plan, hipStream
     body.sync_slots = tail.sync_slots = kSyncSlots / 2;   // each launch of the pair meets on its own counters
     tail.sync = p.sync + kSyncSlots / 2;
   }
+  // A hidden tensor of 4 GiB or more: the 4-wave launch and a general-kernel launch of the same work both go out,
+  // and the flag of the span check decides on the device which of the two does it.
+  KernelParams fallback = paired ? body : p;
+  if (wide) {
+    p.wide_flag = body.wide_flag = fallback.wide_flag = flag;
+    fallback.wide_run_if = 1;
+  }
   int rc = 0;
   for (int c = 0; c < plan.num_chunks; ++c) {
     const int64_t row0 = (int64_t)c * plan.rows_per_chunk;
@@ -912,22 +973,26 @@ int launch_masked_logits(const LogitsArgs& a, const mosaic_plan& plan, hipStream
     int64_t grid = tiles * q.splits;
     const bool several_rounds = grid > plan.grid || (paired && tiles > plan.grid);
     if (grid > plan.grid) grid = plan.grid;
-    if (several_rounds) rc |= launch_kernel(clear_round_counters_kernel, dim3(1), dim3(256), stream, p.sync, kSyncSlots);
-    if ((fast || paired) && sample)
-      rc |= launch_kernel(masked_logits_kernel_w4<true>, dim3((unsigned)grid), dim3(256), stream, q);
-    else if (fast || paired)
-      rc |= launch_kernel(masked_logits_kernel_w4<false>, dim3((unsigned)grid), dim3(256), stream, q);
-    else if (sample)
-      rc |= launch_kernel(masked_logits_kernel<3, 2, true>, dim3((unsigned)grid), dim3(kThreads), stream, p);
-    else
-      rc |= launch_kernel(masked_logits_kernel<3, 2, false>, dim3((unsigned)grid), dim3(kThreads), stream, p);
-    if (paired) {
-      const int64_t tgrid = tiles < plan.grid ? tiles : plan.grid;
-      if (sample)
-        rc |= launch_kernel(masked_logits_kernel<3, 2, true>, dim3((unsigned)tgrid), dim3(kThreads), stream, tail);
-      else
-        rc |= launch_kernel(masked_logits_kernel<3, 2, false>, dim3((unsigned)tgrid), dim3(kThreads), stream, tail);
+    if (several_rounds || wide)
+      rc |= launch_kernel(clear_round_counters_kernel, dim3(1), dim3(256), stream, p.sync, kSyncSlots + 1);
+    if (wide)
+      rc |= launch_kernel(span_check_kernel, dim3((unsigned)((cap + 255) / 256)), dim3(256), stream, a.idx, a.count,
+                          (int32_t)row0, plan.rows_per_chunk, (int32_t)a.max_rows, (int32_t)a.T, p.ldh_bytes, flag);
+    auto launch_general = [&](const KernelParams& kp, int64_t blocks) {
+      return sample ? launch_kernel(masked_logits_kernel<3, 2, true>, dim3((unsigned)blocks), dim3(kThreads), stream, kp)
+                    : launch_kernel(masked_logits_kernel<3, 2, false>, dim3((unsigned)blocks), dim3(kThreads), stream, kp);
+    };
+    if (fast || paired) {
+      rc |= sample ? launch_kernel(masked_logits_kernel_w4<true>, dim3((unsigned)grid), dim3(256), stream, q)
+                   : launch_kernel(masked_logits_kernel_w4<false>, dim3((unsigned)grid), dim3(256), stream, q);
+      if (wide) {   // the same work on the general kernel, for lists the span check flags
+        fallback.row0 = (int32_t)row0;
+        rc |= launch_general(fallback, grid);
+      }
+    } else {
+      rc |= launch_general(p, grid);
     }
+    if (paired) rc |= launch_general(tail, tiles < plan.grid ? tiles : plan.grid);
     if (p.splits >= kWideMergeSplits)
       rc |= launch_kernel(combine_kernel<4>, dim3((unsigned)((cap + 3) / 4)), dim3(256), stream, p);
     else

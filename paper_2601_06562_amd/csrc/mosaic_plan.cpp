@@ -47,24 +47,31 @@ int32_t choose_vocab_splits(int64_t row_tiles, int64_t vocab_tiles, int32_t num_
   return best;
 }
 
-// Which kernel(s) serve a call.  The hand-scheduled 4-wave kernel needs whole vocabulary tiles and 32-bit row
-// offsets.  A vocabulary with a ragged last tile is covered by a pair of launches: the 4-wave kernel on the whole
-// tiles with S - 1 splits and the general 8-wave kernel on the last tile as split S - 1.  Everything else (and
-// plans that ask for it) goes to the general kernel alone.
+// Which kernel(s) serve a call.  The hand-scheduled 4-wave kernel needs whole vocabulary tiles and addresses the 64
+// rows a wave copies by 32-bit offsets from the lowest of them: always possible in a hidden tensor smaller than
+// 4 GiB, and in a larger one unless such a group of rows lies 4 GiB or more apart, which only the device can tell
+// (`wide`: both kernels are launched and a flag decides).  A vocabulary with a ragged last tile is covered by a pair
+// of launches: the 4-wave kernel on the whole tiles with S - 1 splits and the general 8-wave kernel on the last
+// tile as split S - 1.  Everything else (and plans that ask for it) goes to the general kernel alone.
 KernelChoice choose_kernel(int64_t T, int64_t ld_h, int32_t d, int32_t V, const mosaic_plan& plan) {
   const int64_t vocab_tiles = ((int64_t)V + MOSAIC_VOCAB_TILE - 1) / MOSAIC_VOCAB_TILE;
   const bool fast_ok = (plan.flags & MOSAIC_PLAN_GENERAL_KERNEL) == 0 &&
-                       (uint64_t)T * (uint64_t)(ld_h * 2) < ((uint64_t)1 << 32) &&
                        (uint64_t)MOSAIC_VOCAB_TILE * (uint64_t)d * 2u < ((uint64_t)1 << 32);
   KernelChoice c;
   c.fast = fast_ok && V % MOSAIC_VOCAB_TILE == 0;
   c.paired = fast_ok && !c.fast && vocab_tiles >= 2 && plan.vocab_splits >= 2;
+  c.wide = (c.fast || c.paired) && (uint64_t)T * (uint64_t)(ld_h * 2) >= ((uint64_t)1 << 32);
   return c;
 }
 
 const char* masked_logits_kernel_name(int64_t T, int64_t ld_h, int32_t d, int32_t V, const mosaic_plan& plan,
                                       bool sample) {
   const KernelChoice c = choose_kernel(T, ld_h, d, V, plan);
+  if (c.wide)
+    return sample ? "masked_logits_kernel_w4<true>, or masked_logits_kernel<3,2,true> where 64 consecutive rows of "
+                    "the list lie 4 GiB apart (decided on the device)"
+                  : "masked_logits_kernel_w4<false>, or masked_logits_kernel<3,2,false> where 64 consecutive rows of "
+                    "the list lie 4 GiB apart (decided on the device)";
   if (c.fast) return sample ? "masked_logits_kernel_w4<true>" : "masked_logits_kernel_w4<false>";
   if (c.paired)
     return sample ? "masked_logits_kernel_w4<true> + masked_logits_kernel<3,2,true> (ragged last vocabulary tile)"

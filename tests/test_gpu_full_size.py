@@ -71,27 +71,60 @@ def test_full_size_workload(name):
                              what=name + " unmasked rows")
 
 
-def test_hidden_tensor_beyond_4_gib_uses_64_bit_row_offsets():
-    """A hidden tensor larger than 4 GiB: the masked rows sit past the 4 GiB mark, where a 32-bit byte offset wraps.
-    (Such shapes are routed to the general kernel, which addresses rows with 64-bit pointers.)"""
+def span_flag(op):
+    """The word the device-side span check leaves behind the round counters: 1 if some 64 consecutive rows of the
+    list lay 4 GiB or more apart (the general kernel then did the work), 0 if the 4-wave kernel did."""
+    return int(op.workspace[op.plan.workspace_bytes - 4:op.plan.workspace_bytes].view(torch.int32).item())
+
+
+def test_hidden_tensor_beyond_4_gib():
+    """A hidden tensor larger than 4 GiB, where a 32-bit byte offset from the start of the tensor wraps.  The 4-wave
+    kernel addresses a wave's 64 rows from the lowest of them, so it serves such a tensor as long as no 64 consecutive
+    rows of the list lie 4 GiB apart (decided on the device); a list with such a gap goes to the general kernel,
+    which addresses rows with 64-bit pointers.  Both lists here, greedy and sampled, against the oracle."""
     import oracle
+    from paper_2601_06562_amd import binding
     T, d, V = (1 << 19) + 4096, 4096, 1024                  # 4.03 GiB of bf16 hidden states
     print(f"beyond-4GiB hidden: T={T} d={d} V={V}", flush=True)
     gen = torch.Generator(device=DEV)
     gen.manual_seed(workloads.BASE_SEED + 77)
     hidden = workloads._normal_bf16(T, d, 1.0, gen, torch.device(DEV))
     w = workloads._normal_bf16(V, d, d ** -0.5, gen, torch.device(DEV))
-    mask = torch.zeros(T, dtype=torch.uint8, device=DEV)
-    pos = torch.cat([torch.arange(5, 40, 7), torch.arange((1 << 19) - 3, (1 << 19) + 300, 1), torch.tensor([T - 1])])
-    mask[pos.to(DEV)] = 1
-    assert int(pos.max()) * d * 2 > (1 << 32)
-    out = run_hip(hidden, w, mask, max_rows=int(pos.numel()))
-    M = out["M"]
-    assert M == pos.numel() and np.array_equal(out["idx"][:M], np.sort(pos.numpy()).astype(np.int32))
-    want = oracle_rows(hidden, workloads.bf16_bits(w), out["idx"][:M])
-    stats = check_against_oracle(dict(tok=out["tok"][:M], conf=out["conf"][:M], lse=out["lse"][:M]), want,
-                                 what="beyond 4 GiB")
-    print(stats, flush=True)
+    w_bits = workloads.bf16_bits(w)
+    name = binding.mosaic_masked_logits_kernel_name(T, d, d, V, binding.mosaic_plan_workspace(T, 512, d, V), False)
+    assert "masked_logits_kernel_w4<false>" in name and "masked_logits_kernel<3,2,false>" in name
+    far = torch.cat([torch.arange(5, 40, 7), torch.arange((1 << 19) - 3, (1 << 19) + 300, 1), torch.tensor([T - 1])])
+    near = torch.cat([torch.arange((1 << 19) - 350, (1 << 19) + 350, 1), torch.arange(T - 300, T, 1)])
+    for what, pos, flag in (("a gap of 4 GiB inside one group of rows", far, 1), ("rows close together", near, 0)):
+        print(f"beyond-4GiB hidden: {what}", flush=True)
+        mask = torch.zeros(T, dtype=torch.uint8, device=DEV)
+        mask[pos.to(DEV)] = 1
+        assert int(pos.max()) * d * 2 > (1 << 32)
+        out = run_hip(hidden, w, mask, max_rows=int(pos.numel()))
+        M = out["M"]
+        assert M == pos.numel() and np.array_equal(out["idx"][:M], np.sort(pos.numpy()).astype(np.int32))
+        assert span_flag(out["op"]) == flag
+        rows = np.arange(M) if M <= 320 else np.unique(np.concatenate([np.arange(0, M, 5), np.arange(690, 720)]))
+        want = oracle_rows(hidden, w_bits, out["idx"][rows])
+        stats = check_against_oracle(dict(tok=out["tok"][rows], conf=out["conf"][rows], lse=out["lse"][rows]), want,
+                                     what="beyond 4 GiB, " + what)
+        print(stats, flush=True)
+        # the same list under sampling
+        tau, seed = 0.9, 4321
+        op = binding.MaskOnlyLogits(T, d, V, max_rows=M, device=DEV, sampling=True)
+        op.sample_step(hidden, w, mask, tau, seed)
+        torch.cuda.synchronize()
+        assert span_flag(op) == flag
+        tok, lse = op.token.cpu().numpy(), op.lse.cpu().numpy()
+        strict = 0
+        for j in rows[::4]:
+            x = oracle.row_logits(workloads.bf16_bits(hidden[int(out["idx"][j])]), w_bits)
+            tok_o, conf_o, lse_o, gap_o = oracle.row_sample(x, tau, seed, int(out["idx"][j]))
+            assert abs(float(lse[j]) - lse_o) <= 2e-3
+            if gap_o > 1e-3 * (1 + tau):
+                strict += 1
+                assert int(tok[j]) == tok_o, (what, j, int(tok[j]), tok_o, gap_o)
+        assert strict >= 0.8 * len(rows[::4])
     del hidden
     torch.cuda.empty_cache()
 
