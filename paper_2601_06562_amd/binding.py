@@ -471,6 +471,18 @@ class MaskOnlyLogits:
         self.conf = torch.empty(n, dtype=torch.float32, device=dev)
         self.lse = torch.empty(n, dtype=torch.float32, device=dev)
 
+    def replan(self, max_rows, budget_bytes=0):
+        """A new plan for a smaller bound on the masked rows (the host knows how many masks are left: paper section
+        4.4), so that few rows are spread over more vocabulary splits and still fill the chip.  Buffers are kept; the
+        partials workspace grows if the new plan needs more."""
+        if not 0 <= max_rows <= self.token.numel():
+            raise ValueError("max_rows must lie between 0 and the bound the buffers were made for")
+        sampling = bool(self.plan.flags & PLAN_SAMPLING)
+        self.max_rows = max_rows
+        self.plan = mosaic_plan_workspace(self.T, max_rows, self.d, self.V, budget_bytes, sampling=sampling)
+        if self.plan.workspace_bytes > self.workspace.numel():
+            self.workspace = torch.empty(self.plan.workspace_bytes, dtype=torch.uint8, device=self.workspace.device)
+
     @property
     def workspace_bytes(self) -> int:
         """Every device byte the path holds beyond its inputs and its three outputs."""

@@ -128,3 +128,30 @@ def test_denoising_tail_loop_runs_to_completion():
     assert steps == steps_needed
     final = tokens.cpu().numpy()
     assert np.all(final[m0 != 0] >= 0) and np.all(final[m0 == 0] == -1)      # exactly the masked positions were filled
+
+
+def test_replanning_for_the_masks_that_remain_changes_the_schedule_not_the_results():
+    """A scheduler that knows how many masks are left renews the plan (more vocabulary splits for fewer rows); the
+    buffers stay, and the results are those of an object made for that bound."""
+    print("replan", flush=True)
+    T, d, V = 3000, 256, 16384
+    wl = workloads.small_random(T, d, V, p=0.9, seed=5, device=DEV)
+    op = binding.MaskOnlyLogits(T, d, V, device=DEV)
+    mask = wl.mask.clone()
+    splits = []
+    for keep in (2500, 900, 200, 30):
+        pos = torch.nonzero(mask).flatten()
+        mask[pos[keep:]] = 0                                   # fewer masks each round
+        M = int(mask.sum().item())
+        op.replan(M)
+        splits.append(op.plan.vocab_splits)
+        op.step(wl.hidden, wl.w, mask)
+        fresh = binding.MaskOnlyLogits(T, d, V, max_rows=M, device=DEV)
+        fresh.step(wl.hidden, wl.w, mask)
+        torch.cuda.synchronize()
+        assert int(op.count.item()) == M == keep
+        assert torch.equal(op.token[:M], fresh.token[:M]) and torch.equal(op.lse[:M], fresh.lse[:M])
+        assert torch.equal(op.conf[:M], fresh.conf[:M])
+    assert splits[-1] > splits[0]
+    with pytest.raises(ValueError):
+        op.replan(T + 1)
