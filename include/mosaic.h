@@ -98,7 +98,10 @@ typedef struct {
  * really needs.
  *   T          total positions, >= 0, < 2^31
  *   max_rows   host-side upper bound on M (the search in the paper is driven by the
- *              number of masks and the number of tokens; pass T if M is unknown), 0..T
+ *              number of masks and the number of tokens; pass T if M is unknown), 0..T.  Results do
+ *              not depend on it, speed does: the number of vocabulary splits is chosen so that
+ *              max_rows rows fill the chip, so a bound far above the actual M leaves compute units idle
+ *              (planning is a host-side function of a few microseconds: plan again as the masks shrink)
  *   d, V       hidden and vocabulary size; d must be a multiple of MOSAIC_K_TILE
  *   budget_bytes  <= 0 means unbounded
  *   num_cus    compute units to schedule for; <= 0 means 256 (one MI355X)
